@@ -1,0 +1,19 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This package only *makes inputs* (shapes, random draws, dtype encodings, the
+int4 weight quantiser that turns Gaussian weights into packed codes + scales).
+It holds none of the arithmetic of the linear layer itself and imports neither
+the CPU oracle nor the HIP library; both consume what it produces.
+"""
+from .configs import (ProjShape, Workload, WORKLOADS, llama1b_layer_shapes,
+                      ds2d_rows, algorithmic_bytes, algorithmic_flops)
+from .generate import (Problem, make_problem, make_layer, make_rows,
+                       f32_to_bf16_bits, bf16_bits_to_f32, quantise_int4,
+                       pack_nibbles)
+
+__all__ = [
+    "ProjShape", "Workload", "WORKLOADS", "llama1b_layer_shapes", "ds2d_rows",
+    "algorithmic_bytes", "algorithmic_flops", "Problem", "make_problem",
+    "make_layer", "make_rows", "f32_to_bf16_bits", "bf16_bits_to_f32",
+    "quantise_int4", "pack_nibbles",
+]
