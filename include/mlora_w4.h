@@ -1,0 +1,132 @@
+/*
+ * mlora_w4 -- multi-LoRA int4 linear layer for AMD MI355X (gfx950), C ABI.
+ *
+ * One call computes, for a block of M rows (concurrent output streams times
+ * the tokens of a speculative draft tree; paper Sections 3.4 and 3.5),
+ *
+ *     y[m] = dequant(Wq, scales) . x[m]  +  alpha * B[a(m)] . ( A[a(m)] . x[m] )
+ *
+ * which is the paper's LoRA-augmented projection Y = XW + X(sAB) (Section 3.1,
+ * Eq. 1-4) with a frozen int4 base weight (Section 3.3), the LoRA tensors
+ * passed as runtime arguments of identical shape for every adapter (Section
+ * 3.2, approach c; Limitations), and the task selector generalised from "one
+ * LoRA per graph execution" to one adapter index per row.
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller; descriptor
+ *    structs and the arrays of pointers handed to mlora_w4_layer_step are HOST
+ *    memory read during the call.  The library allocates no device memory,
+ *    creates no stream and never synchronises: work is enqueued on `stream`
+ *    (a hipStream_t, NULL = default stream) and results are valid once the
+ *    caller has synchronised with it.
+ *  - bf16 / fp16 tensors are arrays of 16-bit patterns.  All tensors are
+ *    dense, row-major in the index order written next to them.
+ *  - Errors a host check can see are reported before anything is launched.
+ *    An adapter index outside [-1, n_adapters) cannot be seen from the host
+ *    without a synchronisation: such a row is computed without adapter
+ *    (mlora_group_rows reports it through *n_seg = -1).
+ *  - Output is a pure function of the inputs: all reductions run in a fixed
+ *    order, so repeated calls return bit-identical results.
+ */
+#ifndef MLORA_W4_H
+#define MLORA_W4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MLORA_OK = 0,
+    MLORA_EINVAL = -1,       /* null pointer, bad enum value, bad count */
+    MLORA_ESHAPE = -2,       /* dimension outside what the kernels support */
+    MLORA_EALIGN = -3,       /* pointer not 16-byte aligned */
+    MLORA_EWORKSPACE = -4,   /* workspace missing or smaller than mlora_w4_workspace_bytes */
+    MLORA_EUNSUPPORTED = -5, /* valid request this build does not implement */
+    MLORA_EHIP = -6          /* a HIP runtime call failed */
+} mlora_status;
+
+enum { MLORA_Y_BF16 = 0, MLORA_Y_FP32 = 1 };
+
+/* Limits checked on the host (MLORA_ESHAPE otherwise). */
+enum {
+    MLORA_MAX_ROWS = 4096,      /* M */
+    MLORA_MAX_ADAPTERS = 1024,  /* n_adapters */
+    MLORA_MAX_RANK = 128        /* rank; must also be a multiple of 8 */
+};
+
+/* One projection.  K = input features, N = output features.
+ *   K % 128 == 0, group in {32, 64, 128}, N >= 1.
+ *   w_blob   prepacked base weight made by mlora_w4_prepack (opaque, mlora_w4_blob_bytes bytes)
+ *   lora_a   bf16 [n_adapters][rank][K]     (the paper's LoRA-A, transposed)
+ *   lora_b   bf16 [n_adapters][N][rank]     (the paper's LoRA-B, transposed)
+ *   alpha    the paper's scale factor s: multiplies B.(A.x) directly (no division by rank)
+ * n_adapters == 0 (lora_a, lora_b may then be NULL) means a plain int4 linear layer. */
+typedef struct {
+    int32_t K, N;
+    int32_t group;
+    const void *w_blob;
+    int32_t n_adapters, rank;
+    const void *lora_a;
+    const void *lora_b;
+    float alpha;
+} mlora_w4_proj;
+
+/* Size in bytes of the prepacked blob for a K x N weight (0 if the shape is not supported). */
+size_t mlora_w4_blob_bytes(int32_t K, int32_t N, int32_t group);
+
+/* Canonical int4 weight -> device blob (one-time, weights are frozen; Section 3.2).
+ *   wq          uint8 [N][K/2]: code(n, k) sits in byte k/2 of row n, even k in the low
+ *               nibble, odd k in the high nibble, each nibble a two's-complement value in [-8, 7]
+ *   scales_f16  fp16  [N][K/group]: w(n, k) = code(n, k) * scales(n, k / group)
+ *   w_blob      out, mlora_w4_blob_bytes(K, N, group) bytes, 16-byte aligned */
+mlora_status mlora_w4_prepack(int32_t K, int32_t N, int32_t group, const uint8_t *wq,
+                              const uint16_t *scales_f16, void *w_blob, void *stream);
+
+/* Inverse of prepack, for bit-exact checks: codes int8 [N][K] (may be NULL) and
+ * w_f32 float [N][K] = code * scale, exact in fp32 (may be NULL).  Only K, N, group, w_blob
+ * of *p are read. */
+mlora_status mlora_w4_unpack(const mlora_w4_proj *p, int8_t *codes, float *w_f32, void *stream);
+
+/* Stable grouping of rows by adapter (the selector of Section 3.2 made per-row):
+ *   perm[M]        rows that carry an adapter, adapter ascending then row ascending, followed
+ *                  by the rows with index -1 in ascending order
+ *   seg_adapter[s], seg_start[s] for s < *n_seg: adapter of segment s and its first position in
+ *                  perm; seg_start[*n_seg] = number of rows that carry an adapter.  Callers
+ *                  size seg_adapter for min(M, n_adapters) and seg_start for one more.
+ *   n_seg          number of adapters present, or -1 if an index was outside [-1, n_adapters)
+ * All five arrays are device memory; one int32 for n_seg. */
+mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_adapters,
+                              int32_t *perm, int32_t *seg_adapter, int32_t *seg_start,
+                              int32_t *n_seg, void *stream);
+
+/* Device scratch a call over these projections and M rows needs (256-byte aligned pointer). */
+size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M);
+
+/* One projection.
+ *   x            bf16 [M][K]
+ *   row_adapter  int32 [M], -1 = no adapter for that row; NULL = no adapter for any row
+ *   y            [M][N], bf16 (y_dtype = MLORA_Y_BF16, round to nearest even) or fp32
+ * M == 0 is a no-op.  x, y, the tensors of *p and workspace must not overlap. */
+mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,
+                             int32_t M, void *y, int32_t y_dtype, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* Several independent projections over the same M rows and the same row->adapter index in as
+ * few launches as possible: the seven projections of a decoder block (Section 3.1), or more.
+ *   xs[i], ys[i]  device pointers of projection i (host arrays of n_proj pointers); inputs may
+ *                 be shared (q, k, v read the same rows), outputs may not
+ * Ordering against whatever produces the inputs is the caller's business. */
+mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                 const void *const *xs, void *const *ys,
+                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+const char *mlora_strerror(mlora_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLORA_W4_H */

@@ -1,0 +1,13 @@
+"""mlora_w4 for MI355X: Python binding of the C-ABI library (argument marshalling only).
+
+Every step of the computation runs in the HIP kernels of libmlora_w4.so; nothing here has a
+CPU fallback.  Loading fails loudly if the library has not been built
+(python -c "import __graft_entry__ as g; g.build()").
+"""
+from .binding import (LayerPlan, MloraError, Proj, blob_bytes, group_rows, layer_step, lib_path, linear,
+                      load_library, prepack, strerror, unpack, workspace_bytes,
+                      Y_BF16, Y_FP32, exported_symbols)
+
+__all__ = ["LayerPlan", "MloraError", "Proj", "blob_bytes", "group_rows", "layer_step", "lib_path", "linear",
+           "load_library", "prepack", "strerror", "unpack", "workspace_bytes", "Y_BF16",
+           "Y_FP32", "exported_symbols"]

@@ -1,0 +1,174 @@
+"""ctypes binding of include/mlora_w4.h.  Tensors are torch CUDA(HIP) tensors used as plain
+device buffers; work is enqueued on torch's current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmlora_w4.so")
+_lib = None
+
+Y_BF16, Y_FP32 = 0, 1
+
+exported_symbols = (
+    "mlora_strerror", "mlora_w4_blob_bytes", "mlora_w4_prepack", "mlora_w4_unpack",
+    "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
+)
+
+
+class MloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class _ProjStruct(C.Structure):
+    _fields_ = [("K", C.c_int32), ("N", C.c_int32), ("group", C.c_int32),
+                ("w_blob", C.c_void_p), ("n_adapters", C.c_int32), ("rank", C.c_int32),
+                ("lora_a", C.c_void_p), ("lora_b", C.c_void_p), ("alpha", C.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libmlora_w4.so; raises if it is missing (there is no other implementation)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} not built: run __graft_entry__.build() "
+                              "(hipcc --offload-arch=gfx950)")
+        lib = C.CDLL(_LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        pp = C.POINTER(_ProjStruct)
+        lib.mlora_strerror.restype = C.c_char_p
+        lib.mlora_strerror.argtypes = [C.c_int]
+        lib.mlora_w4_blob_bytes.restype = sz
+        lib.mlora_w4_blob_bytes.argtypes = [i32, i32, i32]
+        lib.mlora_w4_prepack.restype = C.c_int
+        lib.mlora_w4_prepack.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        lib.mlora_w4_unpack.restype = C.c_int
+        lib.mlora_w4_unpack.argtypes = [pp, vp, vp, vp]
+        lib.mlora_group_rows.restype = C.c_int
+        lib.mlora_group_rows.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+        lib.mlora_w4_workspace_bytes.restype = sz
+        lib.mlora_w4_workspace_bytes.argtypes = [pp, i32, i32]
+        lib.mlora_w4_linear.restype = C.c_int
+        lib.mlora_w4_linear.argtypes = [pp, vp, vp, i32, vp, i32, vp, sz, vp]
+        lib.mlora_w4_layer_step.restype = C.c_int
+        lib.mlora_w4_layer_step.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32, i32,
+                                            vp, sz, vp]
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load_library().mlora_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise MloraError(status, where)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+class Proj:
+    """One projection descriptor; keeps the tensors it points to alive."""
+
+    def __init__(self, K: int, N: int, group: int, w_blob, lora_a=None, lora_b=None,
+                 alpha: float = 1.0, n_adapters: Optional[int] = None, rank: Optional[int] = None):
+        self.K, self.N, self.group = int(K), int(N), int(group)
+        self.w_blob, self.lora_a, self.lora_b = w_blob, lora_a, lora_b
+        self.alpha = float(alpha)
+        if lora_a is not None:
+            self.n_adapters = int(lora_a.shape[0]) if n_adapters is None else int(n_adapters)
+            self.rank = int(lora_a.shape[1]) if rank is None else int(rank)
+        else:
+            self.n_adapters = 0 if n_adapters is None else int(n_adapters)
+            self.rank = 0 if rank is None else int(rank)
+
+    def struct(self) -> _ProjStruct:
+        return _ProjStruct(self.K, self.N, self.group, _ptr(self.w_blob), self.n_adapters,
+                           self.rank, _ptr(self.lora_a), _ptr(self.lora_b), self.alpha)
+
+
+def _proj_array(projs: Sequence[Proj]):
+    arr = (_ProjStruct * len(projs))()
+    for i, p in enumerate(projs):
+        arr[i] = p.struct()
+    return arr
+
+
+def blob_bytes(K: int, N: int, group: int) -> int:
+    return int(load_library().mlora_w4_blob_bytes(K, N, group))
+
+
+def prepack(K: int, N: int, group: int, wq, scales_f16, w_blob) -> None:
+    _check(load_library().mlora_w4_prepack(K, N, group, _ptr(wq), _ptr(scales_f16), _ptr(w_blob),
+                                           _stream()), "mlora_w4_prepack")
+
+
+def unpack(proj: Proj, codes=None, w_f32=None) -> None:
+    st = proj.struct()
+    _check(load_library().mlora_w4_unpack(C.byref(st), _ptr(codes), _ptr(w_f32), _stream()),
+           "mlora_w4_unpack")
+
+
+def group_rows(row_adapter, M: int, n_adapters: int, perm, seg_adapter, seg_start, n_seg) -> None:
+    _check(load_library().mlora_group_rows(_ptr(row_adapter), M, n_adapters, _ptr(perm),
+                                           _ptr(seg_adapter), _ptr(seg_start), _ptr(n_seg),
+                                           _stream()), "mlora_group_rows")
+
+
+def workspace_bytes(projs: Sequence[Proj], M: int) -> int:
+    arr = _proj_array(projs)
+    return int(load_library().mlora_w4_workspace_bytes(arr, len(projs), M))
+
+
+def linear(proj: Proj, x, row_adapter, M: int, y, y_dtype: int = Y_BF16, workspace=None) -> None:
+    st = proj.struct()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().mlora_w4_linear(C.byref(st), _ptr(x), _ptr(row_adapter), M, _ptr(y),
+                                          y_dtype, _ptr(workspace), ws_bytes, _stream()),
+           "mlora_w4_linear")
+
+
+class LayerPlan:
+    """Marshalled arguments of a layer_step call, reusable across calls (no per-call Python
+    allocation in timing loops)."""
+
+    def __init__(self, projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,
+                 y_dtype: int, workspace):
+        assert len(projs) == len(xs) == len(ys)
+        self.keep = (list(projs), list(xs), list(ys), row_adapter, workspace)
+        self.n = len(projs)
+        self.arr = _proj_array(projs)
+        self.xs = (C.c_void_p * self.n)(*[_ptr(x) for x in xs])
+        self.ys = (C.c_void_p * self.n)(*[_ptr(y) for y in ys])
+        self.rows = _ptr(row_adapter)
+        self.M, self.y_dtype = int(M), int(y_dtype)
+        self.ws = _ptr(workspace)
+        self.ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self.fn = load_library().mlora_w4_layer_step
+
+    def run(self, stream: Optional[int] = None) -> None:
+        st = self.fn(self.arr, self.n, self.xs, self.ys, self.rows, self.M, self.y_dtype,
+                     self.ws, self.ws_bytes, _stream() if stream is None else stream)
+        if st != 0:
+            raise MloraError(st, "mlora_w4_layer_step")
+
+
+def layer_step(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,
+               y_dtype: int = Y_BF16, workspace=None) -> None:
+    LayerPlan(projs, xs, ys, row_adapter, M, y_dtype, workspace).run()

@@ -1,0 +1,211 @@
+// C ABI of the mlora_w4 library: host-side validation, launch planning, no device allocation.
+#include <string.h>
+
+#include "common.hpp"
+
+using namespace mlora;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+mlora_status check_weight_shape(int K, int N, int group)
+{
+    if (group != 32 && group != 64 && group != 128) return MLORA_ESHAPE;
+    if (K <= 0 || N <= 0 || K % SUPER_K != 0) return MLORA_ESHAPE;
+    if ((long long)N > (1ll << 24) || (long long)K > (1ll << 24)) return MLORA_ESHAPE;
+    return MLORA_OK;
+}
+
+mlora_status check_proj(const mlora_w4_proj &p)
+{
+    mlora_status st = check_weight_shape(p.K, p.N, p.group);
+    if (st != MLORA_OK) return st;
+    if (!p.w_blob) return MLORA_EINVAL;
+    if (!aligned16(p.w_blob)) return MLORA_EALIGN;
+    if (p.n_adapters < 0 || p.n_adapters > MLORA_MAX_ADAPTERS) return MLORA_ESHAPE;
+    if (p.n_adapters > 0) {
+        if (p.rank <= 0 || p.rank > MLORA_MAX_RANK || p.rank % 8 != 0) return MLORA_ESHAPE;
+        if (!p.lora_a || !p.lora_b) return MLORA_EINVAL;
+        if (!aligned16(p.lora_a) || !aligned16(p.lora_b)) return MLORA_EALIGN;
+    }
+    return MLORA_OK;
+}
+
+int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 16 * 16 : 0; }
+int kch_of(const mlora_w4_proj &p)
+{
+    int c = p.K / 512;
+    return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
+}
+size_t t_part_bytes(const mlora_w4_proj &p, int M)
+{
+    return round_up((size_t)kch_of(p) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
+}
+
+// upper bound of the number of 16-row tiles the adapter segments of M rows can form
+int max_row_tiles(int M, int n_adapters)
+{
+    const int segs = n_adapters < M ? n_adapters : M;
+    const int bound = M / 16 + segs;
+    return bound < M ? bound : M;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mlora_strerror(mlora_status status)
+{
+    switch (status) {
+    case MLORA_OK: return "ok";
+    case MLORA_EINVAL: return "invalid argument (null pointer, bad enum or count)";
+    case MLORA_ESHAPE: return "unsupported shape (K % 128, group in {32,64,128}, rank % 8, limits)";
+    case MLORA_EALIGN: return "pointer not 16-byte aligned";
+    case MLORA_EWORKSPACE: return "workspace missing or too small";
+    case MLORA_EUNSUPPORTED: return "not implemented in this build";
+    case MLORA_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t mlora_w4_blob_bytes(int32_t K, int32_t N, int32_t group)
+{
+    if (check_weight_shape(K, N, group) != MLORA_OK) return 0;
+    return blob_code_bytes(K, N) + blob_scale_bytes(K, N, group);
+}
+
+mlora_status mlora_w4_prepack(int32_t K, int32_t N, int32_t group, const uint8_t *wq,
+                              const uint16_t *scales_f16, void *w_blob, void *stream)
+{
+    mlora_status st = check_weight_shape(K, N, group);
+    if (st != MLORA_OK) return st;
+    if (!wq || !scales_f16 || !w_blob) return MLORA_EINVAL;
+    if (!aligned16(wq) || !aligned16(scales_f16) || !aligned16(w_blob)) return MLORA_EALIGN;
+    return launch_prepack(K, N, group, wq, scales_f16, w_blob, (hipStream_t)stream) == hipSuccess
+               ? MLORA_OK : MLORA_EHIP;
+}
+
+mlora_status mlora_w4_unpack(const mlora_w4_proj *p, int8_t *codes, float *w_f32, void *stream)
+{
+    if (!p) return MLORA_EINVAL;
+    mlora_status st = check_weight_shape(p->K, p->N, p->group);
+    if (st != MLORA_OK) return st;
+    if (!p->w_blob || (!codes && !w_f32)) return MLORA_EINVAL;
+    if (!aligned16(p->w_blob)) return MLORA_EALIGN;
+    return launch_unpack(p->K, p->N, p->group, p->w_blob, codes, w_f32, (hipStream_t)stream) == hipSuccess
+               ? MLORA_OK : MLORA_EHIP;
+}
+
+mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_adapters,
+                              int32_t *perm, int32_t *seg_adapter, int32_t *seg_start,
+                              int32_t *n_seg, void *stream)
+{
+    if (!perm || !seg_adapter || !seg_start || !n_seg) return MLORA_EINVAL;
+    if (M < 0 || M > MLORA_MAX_ROWS || n_adapters < 1 || n_adapters > MLORA_MAX_ADAPTERS)
+        return MLORA_ESHAPE;
+    if (M > 0 && !row_adapter) return MLORA_EINVAL;
+    return launch_group_rows(row_adapter, M, n_adapters, perm, seg_adapter, seg_start, n_seg,
+                             (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
+}
+
+size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M)
+{
+    if (!projs || n_proj <= 0 || M <= 0) return 0;
+    size_t total = 0;
+    for (int i = 0; i < n_proj; ++i) total += t_part_bytes(projs[i], M);
+    return total;
+}
+
+mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                 const void *const *xs, void *const *ys,
+                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!projs || !xs || !ys || n_proj <= 0) return MLORA_EINVAL;
+    if (y_dtype != MLORA_Y_BF16 && y_dtype != MLORA_Y_FP32) return MLORA_EINVAL;
+    if (M < 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
+    bool any_lora = false;
+    for (int i = 0; i < n_proj; ++i) {
+        mlora_status st = check_proj(projs[i]);
+        if (st != MLORA_OK) return st;
+        if (!xs[i] || !ys[i]) return MLORA_EINVAL;
+        if (!aligned16(xs[i]) || !aligned16(ys[i])) return MLORA_EALIGN;
+        for (int j = 0; j < i; ++j)
+            if (ys[j] == ys[i]) return MLORA_EINVAL;
+        any_lora = any_lora || projs[i].n_adapters > 0;
+    }
+    if (M == 0) return MLORA_OK;
+    any_lora = any_lora && row_adapter != nullptr;
+    if (row_adapter && (reinterpret_cast<uintptr_t>(row_adapter) & 3u)) return MLORA_EALIGN;
+    if (any_lora) {
+        const size_t need = mlora_w4_workspace_bytes(projs, n_proj, M);
+        if (!workspace || workspace_bytes < need) return MLORA_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
+    }
+
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = reinterpret_cast<char *>(workspace);
+    for (int first = 0; first < n_proj; first += MAX_PROJ_PER_LAUNCH) {
+        const int count = (n_proj - first < MAX_PROJ_PER_LAUNCH) ? n_proj - first : MAX_PROJ_PER_LAUNCH;
+        LayerArgs a;
+        memset(&a, 0, sizeof a);
+        a.row_adapter = any_lora ? row_adapter : nullptr;
+        a.n_proj = count;
+        a.M = M;
+        a.y_fp32 = (y_dtype == MLORA_Y_FP32);
+        int tiles = 0, shrink_blocks = 0, max_tiles = 0;
+        for (int i = 0; i < count; ++i) {
+            const mlora_w4_proj &p = projs[first + i];
+            ProjArgs &d = a.p[i];
+            d.codes = reinterpret_cast<const uint4 *>(p.w_blob);
+            d.scales = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(p.w_blob) +
+                                                       blob_code_bytes(p.K, p.N));
+            d.x = reinterpret_cast<const uint16_t *>(xs[first + i]);
+            d.y = ys[first + i];
+            d.K = p.K;
+            d.N = p.N;
+            d.spg = p.group / KSTEP;
+            d.alpha = p.alpha;
+            d.tile_begin = tiles;
+            tiles += tiles_n(p.N);
+            d.shrink_begin = shrink_blocks;
+            if (any_lora && p.n_adapters > 0) {
+                d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);
+                d.lora_b = reinterpret_cast<const uint16_t *>(p.lora_b);
+                d.n_adapters = p.n_adapters;
+                d.rank = p.rank;
+                d.r16 = r16_of(p);
+                d.kch = kch_of(p);
+                d.t_part = reinterpret_cast<float *>(ws);
+                ws += t_part_bytes(p, M);
+                const int mt = max_row_tiles(M, p.n_adapters);
+                if (mt > max_tiles) max_tiles = mt;
+                shrink_blocks += mt * (d.r16 / 16) * d.kch;
+            } else {
+                d.n_adapters = 0;
+                d.rank = 0;
+                d.r16 = 16;
+                d.kch = 1;
+            }
+        }
+        a.max_row_tiles = max_tiles;
+        if (shrink_blocks > 0 && launch_shrink(a, shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
+        if (launch_base(a, tiles, s) != hipSuccess) return MLORA_EHIP;
+    }
+    return MLORA_OK;
+}
+
+mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,
+                             int32_t M, void *y, int32_t y_dtype, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    if (!p) return MLORA_EINVAL;
+    const void *xs[1] = {x};
+    void *ys[1] = {y};
+    return mlora_w4_layer_step(p, 1, xs, ys, row_adapter, M, y_dtype, workspace, workspace_bytes,
+                               stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Shared device-side definitions of the mlora_w4 library: blob layout, kernel
+// argument blocks, small bit helpers.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mlora_w4.h"
+
+namespace mlora {
+
+// ---------------------------------------------------------------------------------------------
+// Prepacked weight blob.
+//
+// The weight is cut into tiles of 64 output columns (4 blocks of 16) and k-steps of 32 inputs:
+// one 16x16x32 bf16 MFMA consumes a block of 16 columns x 32 inputs as its B operand, lane l
+// holding column l%16 and the 8 consecutive inputs 8*(l/16) .. +7.  The blob stores, for
+// every (tile, k-step), one 1 KiB chunk laid out exactly as a wavefront reads it with one
+// 128-bit load per lane: lane l's uint4 holds, in component j, the 8 codes of column
+// 64*tile + 16*j + l%16 at inputs 32*step + 8*(l/16) + 0..7.
+//
+// Inside a dword the 8 codes are stored as offset-binary u = code + 8 in bit fields placed so
+// that  ((w rotr 4q) & 0x00780078) | 0x41804180  is a pair of bf16 numbers 16 + u = code + 24
+// for inputs 2q (low half) and 2q+1 (high half): the field of input i sits at bit
+// (3 + 4*(i/2) + 16*(i%2)) mod 32.  The constant offset 24 is removed by seeding the MFMA
+// accumulator with -24 * sum(x) over the same inputs, which one more MFMA produces.
+//
+// Scales follow the codes: fp16, index ((tile * K/group + g) * 16 + c) * 4 + j for column
+// 64*tile + 16*j + c, so the lane that holds column c of all four blocks reads its four
+// scales of a group with one 64-bit load.  Columns beyond N are stored as code 0, scale 0.
+// ---------------------------------------------------------------------------------------------
+constexpr int TILE_N = 64;
+constexpr int KSTEP = 32;
+constexpr int SUPER_K = 128;       // k-steps are consumed four at a time
+
+__host__ __device__ inline int tiles_n(int N) { return (N + TILE_N - 1) / TILE_N; }
+__host__ __device__ inline size_t blob_code_bytes(int K, int N) {
+    return (size_t)tiles_n(N) * (size_t)(K / KSTEP) * 1024u;
+}
+__host__ __device__ inline size_t blob_scale_bytes(int K, int N, int group) {
+    return (size_t)tiles_n(N) * (size_t)(K / group) * 128u;
+}
+__host__ __device__ inline int field_pos(int i) { return (3 + 4 * (i >> 1) + 16 * (i & 1)) & 31; }
+__host__ __device__ inline uint32_t rotl32(uint32_t v, int s) {
+    s &= 31;
+    return s ? (v << s) | (v >> (32 - s)) : v;
+}
+__host__ __device__ inline uint32_t rotr32(uint32_t v, int s) { return rotl32(v, 32 - (s & 31)); }
+
+// ---------------------------------------------------------------------------------------------
+// Kernel argument block of one grouped call (passed by value, < 4 KiB).
+// ---------------------------------------------------------------------------------------------
+constexpr int MAX_PROJ_PER_LAUNCH = 16;
+constexpr int ROWS_PER_BLOCK16 = 16;
+constexpr int MAX_KCHUNKS = 8;     // partial sums of the shrink step the epilogue adds up
+
+struct ProjArgs {
+    const uint4 *codes;        // blob, code region
+    const uint2 *scales;       // blob, scale region (4 fp16 per entry)
+    const uint16_t *x;         // bf16 [M][K]
+    void *y;                   // [M][N]
+    const uint16_t *lora_a;    // bf16 [n_adapters][rank][K]
+    const uint16_t *lora_b;    // bf16 [n_adapters][N][rank]
+    float *t_part;             // fp32 [kch][M][r16], written by the shrink kernel
+    int K, N;
+    int spg;                   // k-steps per scale group (group / 32)
+    int n_adapters, rank;
+    int r16;                   // rank rounded up to a multiple of 16
+    int kch;                   // number of K chunks of the shrink step
+    float alpha;
+    int tile_begin;            // first block index of this projection in the base kernel
+    int shrink_begin;          // first block index of this projection in the shrink kernel
+};
+
+struct LayerArgs {
+    ProjArgs p[MAX_PROJ_PER_LAUNCH];
+    const int *row_adapter;    // may be null
+    int n_proj;
+    int M;
+    int y_fp32;
+    int max_row_tiles;         // upper bound of 16-row tiles of adapter segments
+};
+
+// ---------------------------------------------------------------------------------------------
+// 16-bit float helpers (bit patterns)
+// ---------------------------------------------------------------------------------------------
+__device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ inline uint16_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                                              // nearest even
+    return (uint16_t)(u >> 16);
+}
+
+__device__ inline float half_bits_to_float(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// D[16 rows][16 cols] += A[16][32] * B[32][16]; lane l supplies row l%16 of A and column l%16
+// of B at inputs 8*(l/16)..+7, and receives D[4*(l/16) + r][l%16] in element r.
+__device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+
+// host launchers (each file defines its own)
+hipError_t launch_prepack(int K, int N, int group, const uint8_t *wq, const uint16_t *scales,
+                          void *blob, hipStream_t s);
+hipError_t launch_unpack(int K, int N, int group, const void *blob, int8_t *codes, float *w_f32,
+                         hipStream_t s);
+hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int *perm,
+                             int *seg_adapter, int *seg_start, int *n_seg, hipStream_t s);
+hipError_t launch_shrink(const LayerArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_base(const LayerArgs &a, int n_tiles, hipStream_t s);
+
+}  // namespace mlora

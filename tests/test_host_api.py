@@ -1,0 +1,120 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header declares,
+sizes blobs and workspaces as documented, and rejects bad arguments on the host before any
+launch (so none of these calls touches a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2604_18655_amd as lib
+from paper_2604_18655_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE = 0, -1, -2, -3, -4
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "mlora_w4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mlora_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    cdll = lib.load_library()
+    names = header_functions()
+    assert set(names) == set(lib.exported_symbols)
+    for name in names:
+        assert getattr(cdll, name) is not None
+
+
+def test_strerror_covers_all_codes():
+    texts = {lib.strerror(c) for c in range(0, -7, -1)}
+    assert len(texts) == 7 and "unknown" not in " ".join(texts)
+    assert "unknown" in lib.strerror(-99)
+
+
+def test_blob_bytes():
+    # codes: ceil(N/64) tiles x K/32 steps x 1 KiB; scales: tiles x K/group x 128 B
+    assert lib.blob_bytes(256, 256, 32) == 4 * 8 * 1024 + 4 * 8 * 128
+    assert lib.blob_bytes(256, 200, 64) == 4 * 8 * 1024 + 4 * 4 * 128
+    assert lib.blob_bytes(2048, 8192, 32) == 8192 * 2048 // 2 + 8192 * 64 * 2
+    for bad in [(100, 64, 32), (256, 64, 16), (256, 0, 32), (0, 64, 32), (64, 64, 32)]:
+        assert lib.blob_bytes(*bad) == 0
+
+
+def proj(K=256, N=64, group=32, blob=0x1000, n_ad=2, rank=8, a=0x2000, b=0x3000, alpha=1.0):
+    return binding._ProjStruct(K, N, group, blob, n_ad, rank, a, b, alpha)
+
+
+def test_workspace_bytes():
+    cdll = lib.load_library()
+    p = proj(K=2048, rank=16)
+    # K/512 = 4 chunks x M x rank16 x 4 bytes, rounded up to 256
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 4 * 8 * 16 * 4
+    p = proj(K=256, rank=8)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == 256
+    p = proj(K=16384, rank=64)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == 8 * 64 * 64 * 4
+    p = proj(n_ad=0, rank=0, a=None, b=None)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 0
+
+
+def call_linear(p, x=0x4000, rows=0x5000, M=4, y=0x6000, y_dtype=0, ws=0x7000, ws_bytes=1 << 20):
+    return lib.load_library().mlora_w4_linear(C.byref(p), x, rows, M, y, y_dtype, ws, ws_bytes, None)
+
+
+def test_linear_rejects_bad_arguments_before_launch():
+    assert call_linear(proj(K=100)) == ESHAPE
+    assert call_linear(proj(K=192)) == ESHAPE                 # K % 128
+    assert call_linear(proj(group=48)) == ESHAPE
+    assert call_linear(proj(N=0)) == ESHAPE
+    assert call_linear(proj(rank=12)) == ESHAPE
+    assert call_linear(proj(rank=136)) == ESHAPE
+    assert call_linear(proj(n_ad=1025)) == ESHAPE
+    assert call_linear(proj(), M=4097) == ESHAPE
+    assert call_linear(proj(), M=-1) == ESHAPE
+    assert call_linear(proj(blob=None)) == EINVAL
+    assert call_linear(proj(a=None)) == EINVAL
+    assert call_linear(proj(), x=None) == EINVAL
+    assert call_linear(proj(), y=None) == EINVAL
+    assert call_linear(proj(), y_dtype=2) == EINVAL
+    assert call_linear(proj(blob=0x1008)) == EALIGN
+    assert call_linear(proj(b=0x3004)) == EALIGN
+    assert call_linear(proj(), x=0x4002) == EALIGN
+    assert call_linear(proj(), ws=0x7010) == EALIGN           # workspace wants 256 bytes
+    assert call_linear(proj(), ws=None) == EWORKSPACE
+    assert call_linear(proj(), ws_bytes=16) == EWORKSPACE
+    assert call_linear(proj(), M=0) == OK                     # empty call: nothing to launch
+    assert lib.load_library().mlora_w4_linear(None, 1, 1, 1, 1, 0, 1, 1, None) == EINVAL
+
+
+def test_layer_step_rejects_shared_outputs_and_bad_counts():
+    cdll = lib.load_library()
+    arr = (binding._ProjStruct * 2)(proj(), proj())
+    xs = (C.c_void_p * 2)(0x4000, 0x4000)
+    ys = (C.c_void_p * 2)(0x6000, 0x6000)
+    assert cdll.mlora_w4_layer_step(arr, 2, xs, ys, 0x5000, 4, 0, 0x7000, 1 << 20, None) == EINVAL
+    ys = (C.c_void_p * 2)(0x6000, 0x8000)
+    assert cdll.mlora_w4_layer_step(arr, 0, xs, ys, 0x5000, 4, 0, 0x7000, 1 << 20, None) == EINVAL
+    assert cdll.mlora_w4_layer_step(arr, 2, None, ys, 0x5000, 4, 0, 0x7000, 1 << 20, None) == EINVAL
+
+
+def test_prepack_unpack_group_rows_reject_bad_arguments():
+    cdll = lib.load_library()
+    assert cdll.mlora_w4_prepack(256, 64, 32, None, 0x1000, 0x2000, None) == EINVAL
+    assert cdll.mlora_w4_prepack(256, 64, 33, 0x1000, 0x1000, 0x2000, None) == ESHAPE
+    assert cdll.mlora_w4_prepack(256, 64, 32, 0x1001, 0x1000, 0x2000, None) == EALIGN
+    p = proj()
+    assert cdll.mlora_w4_unpack(C.byref(p), None, None, None) == EINVAL
+    assert cdll.mlora_w4_unpack(None, 0x1000, None, None) == EINVAL
+    assert cdll.mlora_group_rows(0x1000, 4, 0, 0x1000, 0x1000, 0x1000, 0x1000, None) == ESHAPE
+    assert cdll.mlora_group_rows(0x1000, 5000, 4, 0x1000, 0x1000, 0x1000, 0x1000, None) == ESHAPE
+    assert cdll.mlora_group_rows(0x1000, 4, 4, None, 0x1000, 0x1000, 0x1000, None) == EINVAL
+    assert cdll.mlora_group_rows(None, 4, 4, 0x1000, 0x1000, 0x1000, 0x1000, None) == EINVAL
+
+
+def test_binding_raises_with_the_library_message():
+    with pytest.raises(lib.MloraError) as e:
+        binding._check(ESHAPE, "mlora_w4_linear")
+    assert "unsupported shape" in str(e.value)
