@@ -124,6 +124,20 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                                  const int32_t *row_adapter, int32_t M, int32_t y_dtype,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same call split at its one internal dependency, for timing each launch on its own:
+ *   MLORA_PHASE_SHRINK  group rows by adapter and compute t[m] = A[a(m)].x[m] (the inner
+ *                       factor of the LoRA term of Eq. 1-4) into the workspace
+ *   MLORA_PHASE_BASE    base product, plus alpha*B[a(m)].t[m] read back from the workspace
+ * phases = MLORA_PHASE_SHRINK | MLORA_PHASE_BASE is mlora_w4_layer_step.  Running
+ * MLORA_PHASE_BASE alone needs the workspace left by a MLORA_PHASE_SHRINK call with the same
+ * arguments. */
+enum { MLORA_PHASE_SHRINK = 1, MLORA_PHASE_BASE = 2 };
+mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_proj,
+                                        const void *const *xs, void *const *ys,
+                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                        void *workspace, size_t workspace_bytes, void *stream,
+                                        int32_t phases);
+
 const char *mlora_strerror(mlora_status status);
 
 #ifdef __cplusplus

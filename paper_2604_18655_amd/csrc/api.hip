@@ -118,12 +118,14 @@ size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int3
     return total;
 }
 
-mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
-                                 const void *const *xs, void *const *ys,
-                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
-                                 void *workspace, size_t workspace_bytes, void *stream)
+mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_proj,
+                                        const void *const *xs, void *const *ys,
+                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                        void *workspace, size_t workspace_bytes, void *stream,
+                                        int32_t phases)
 {
     if (!projs || !xs || !ys || n_proj <= 0) return MLORA_EINVAL;
+    if (phases < 1 || phases > (MLORA_PHASE_SHRINK | MLORA_PHASE_BASE)) return MLORA_EINVAL;
     if (y_dtype != MLORA_Y_BF16 && y_dtype != MLORA_Y_FP32) return MLORA_EINVAL;
     if (M < 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
     bool any_lora = false;
@@ -191,10 +193,21 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             }
         }
         a.max_row_tiles = max_tiles;
-        if (shrink_blocks > 0 && launch_shrink(a, shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
-        if (launch_base(a, tiles, s) != hipSuccess) return MLORA_EHIP;
+        if ((phases & MLORA_PHASE_SHRINK) && shrink_blocks > 0 &&
+            launch_shrink(a, shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
+        if ((phases & MLORA_PHASE_BASE) && launch_base(a, tiles, s) != hipSuccess) return MLORA_EHIP;
     }
     return MLORA_OK;
+}
+
+mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                 const void *const *xs, void *const *ys,
+                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    return mlora_w4_layer_step_phases(projs, n_proj, xs, ys, row_adapter, M, y_dtype, workspace,
+                                      workspace_bytes, stream,
+                                      MLORA_PHASE_SHRINK | MLORA_PHASE_BASE);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,
