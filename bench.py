@@ -75,7 +75,17 @@ def main():
     U = len(set(int(a) for a in rows0 if a >= 0))
     layer_bytes = sum(wl.algorithmic_bytes(p, M, U, ysz) for p in w.projs)
     layer_flops = sum(wl.algorithmic_flops(p, M) for p in w.projs)
-    base_bytes = sum(wl.algorithmic_bytes(p, M, U, ysz) - 2 * U * p.rank * p.K for p in w.projs)
+
+    def main_launch_bytes(p):
+        # what the finishing launch moves: the first K unit of every tile (the library cuts K
+        # into ceil(K/2048) balanced units of 128-input super-steps), x for that slice, B, y, index
+        nss = p.K // 128
+        ksplit = -(-nss // 16)
+        frac = (nss // ksplit + (1 if nss % ksplit else 0)) / nss
+        return int((p.N * p.K // 2 + 2 * p.N * (p.K // p.group) + 2 * M * p.K) * frac
+                   + ysz * M * p.N + 2 * U * p.rank * p.N + 4 * M)
+
+    base_bytes = sum(main_launch_bytes(p) for p in w.projs)
     step_bytes, step_flops = layer_bytes * w.layers, layer_flops * w.layers
 
     # rotating copies: each "copy" is a full set of w.layers layers
@@ -144,9 +154,9 @@ def main():
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
     for e in range(n_ev):
         plan = plans[(args.warmup + e) % n_plans]
-        plan.run_phases(lib.PHASE_SHRINK)
+        plan.run_phases(lib.PHASE_PRE)
         starts[e].record()
-        plan.run_phases(lib.PHASE_BASE)
+        plan.run_phases(lib.PHASE_MAIN)
         stops[e].record()
     torch.cuda.synchronize()
     durs_ms = sorted(s.elapsed_time(t) for s, t in zip(starts, stops))
@@ -189,7 +199,7 @@ def main():
         "tflops": round(step_flops / (elapsed / K) / 1e12, 3),
         "setup_s": round(setup_s, 1),
         "roofline": {
-            "kernel": "base_expand_kernel",
+            "kernel": "layer_main_kernel",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,

@@ -125,13 +125,15 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same call split at its one internal dependency, for timing each launch on its own:
- *   MLORA_PHASE_SHRINK  group rows by adapter and compute t[m] = A[a(m)].x[m] (the inner
- *                       factor of the LoRA term of Eq. 1-4) into the workspace
- *   MLORA_PHASE_BASE    base product, plus alpha*B[a(m)].t[m] read back from the workspace
- * phases = MLORA_PHASE_SHRINK | MLORA_PHASE_BASE is mlora_w4_layer_step.  Running
- * MLORA_PHASE_BASE alone needs the workspace left by a MLORA_PHASE_SHRINK call with the same
- * arguments. */
-enum { MLORA_PHASE_SHRINK = 1, MLORA_PHASE_BASE = 2 };
+ *   MLORA_PHASE_PRE   everything the finishing launch depends on: group rows by adapter and
+ *                     compute t[m] = A[a(m)].x[m] (the inner factor of the LoRA term of Eq. 1-4),
+ *                     plus, for projections with more than 2048 inputs, the partial base
+ *                     products of all but the first 2048-input slice; all left in the workspace
+ *   MLORA_PHASE_MAIN  base product (first slice plus the stored partials) + alpha*B[a(m)].t[m],
+ *                     stores y
+ * phases = MLORA_PHASE_PRE | MLORA_PHASE_MAIN is mlora_w4_layer_step.  MLORA_PHASE_MAIN alone
+ * needs the workspace left by a MLORA_PHASE_PRE call with the same arguments. */
+enum { MLORA_PHASE_PRE = 1, MLORA_PHASE_MAIN = 2 };
 mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_proj,
                                         const void *const *xs, void *const *ys,
                                         const int32_t *row_adapter, int32_t M, int32_t y_dtype,

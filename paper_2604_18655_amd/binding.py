@@ -17,7 +17,7 @@ exported_symbols = (
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
     "mlora_w4_layer_step_phases",
 )
-PHASE_SHRINK, PHASE_BASE = 1, 2
+PHASE_PRE, PHASE_MAIN = 1, 2
 
 
 class MloraError(RuntimeError):

@@ -36,12 +36,23 @@ mlora_status check_proj(const mlora_w4_proj &p)
 int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 16 * 16 : 0; }
 int kch_of(const mlora_w4_proj &p)
 {
-    int c = p.K / 512;
+    int c = p.K / 512;   // at least 512 inputs per chunk, at most MAX_KCHUNKS chunks
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 size_t t_part_bytes(const mlora_w4_proj &p, int M)
 {
     return round_up((size_t)kch_of(p) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
+}
+
+int ksplit_of(const mlora_w4_proj &p)
+{
+    const int nss = p.K / SUPER_K;
+    return (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
+}
+int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
+size_t partial_bytes(const mlora_w4_proj &p, int M)
+{
+    return (size_t)(ksplit_of(p) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
 }
 
 // upper bound of the number of 16-row tiles the adapter segments of M rows can form
@@ -73,7 +84,7 @@ const char *mlora_strerror(mlora_status status)
 size_t mlora_w4_blob_bytes(int32_t K, int32_t N, int32_t group)
 {
     if (check_weight_shape(K, N, group) != MLORA_OK) return 0;
-    return blob_code_bytes(K, N) + blob_scale_bytes(K, N, group);
+    return blob_code_bytes(K, N) + blob_scale_bytes(K, N, group) + BLOB_SLACK_BYTES;
 }
 
 mlora_status mlora_w4_prepack(int32_t K, int32_t N, int32_t group, const uint8_t *wq,
@@ -114,7 +125,7 @@ size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int3
 {
     if (!projs || n_proj <= 0 || M <= 0) return 0;
     size_t total = 0;
-    for (int i = 0; i < n_proj; ++i) total += t_part_bytes(projs[i], M);
+    for (int i = 0; i < n_proj; ++i) total += t_part_bytes(projs[i], M) + partial_bytes(projs[i], M);
     return total;
 }
 
@@ -125,7 +136,7 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
                                         int32_t phases)
 {
     if (!projs || !xs || !ys || n_proj <= 0) return MLORA_EINVAL;
-    if (phases < 1 || phases > (MLORA_PHASE_SHRINK | MLORA_PHASE_BASE)) return MLORA_EINVAL;
+    if (phases < 1 || phases > (MLORA_PHASE_PRE | MLORA_PHASE_MAIN)) return MLORA_EINVAL;
     if (y_dtype != MLORA_Y_BF16 && y_dtype != MLORA_Y_FP32) return MLORA_EINVAL;
     if (M < 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
     bool any_lora = false;
@@ -141,8 +152,8 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
     if (M == 0) return MLORA_OK;
     any_lora = any_lora && row_adapter != nullptr;
     if (row_adapter && (reinterpret_cast<uintptr_t>(row_adapter) & 3u)) return MLORA_EALIGN;
-    if (any_lora) {
-        const size_t need = mlora_w4_workspace_bytes(projs, n_proj, M);
+    const size_t need = mlora_w4_workspace_bytes(projs, n_proj, M);
+    if (need > 0) {
         if (!workspace || workspace_bytes < need) return MLORA_EWORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
     }
@@ -157,7 +168,10 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
         a.n_proj = count;
         a.M = M;
         a.y_fp32 = (y_dtype == MLORA_Y_FP32);
-        int tiles = 0, shrink_blocks = 0, max_tiles = 0;
+        a.m_pad = m_pad_of(M);
+        a.code_mask = 0x00780078u;
+        a.code_bias = 0x41804180u;
+        int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0;
         for (int i = 0; i < count; ++i) {
             const mlora_w4_proj &p = projs[first + i];
             ProjArgs &d = a.p[i];
@@ -170,9 +184,14 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
             d.N = p.N;
             d.spg = p.group / KSTEP;
             d.alpha = p.alpha;
-            d.tile_begin = tiles;
-            tiles += tiles_n(p.N);
-            d.shrink_begin = shrink_blocks;
+            d.ksplit = ksplit_of(p);
+            a.main_begin[i] = main_blocks;
+            main_blocks += tiles_n(p.N);
+            a.pre_begin[i] = pre_blocks;
+            pre_blocks += tiles_n(p.N) * (d.ksplit - 1);
+            d.partial = reinterpret_cast<float *>(ws);
+            ws += partial_bytes(p, M);
+            a.shrink_begin[i] = shrink_blocks;
             if (any_lora && p.n_adapters > 0) {
                 d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);
                 d.lora_b = reinterpret_cast<const uint16_t *>(p.lora_b);
@@ -182,9 +201,7 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
                 d.kch = kch_of(p);
                 d.t_part = reinterpret_cast<float *>(ws);
                 ws += t_part_bytes(p, M);
-                const int mt = max_row_tiles(M, p.n_adapters);
-                if (mt > max_tiles) max_tiles = mt;
-                shrink_blocks += mt * (d.r16 / 16) * d.kch;
+                shrink_blocks += max_row_tiles(M, p.n_adapters) * (d.r16 / 16) * d.kch;
             } else {
                 d.n_adapters = 0;
                 d.rank = 0;
@@ -192,10 +209,10 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
                 d.kch = 1;
             }
         }
-        a.max_row_tiles = max_tiles;
-        if ((phases & MLORA_PHASE_SHRINK) && shrink_blocks > 0 &&
-            launch_shrink(a, shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
-        if ((phases & MLORA_PHASE_BASE) && launch_base(a, tiles, s) != hipSuccess) return MLORA_EHIP;
+        a.pre_base_blocks = pre_blocks;
+        if ((phases & MLORA_PHASE_PRE) && pre_blocks + shrink_blocks > 0 &&
+            launch_pre(a, pre_blocks + shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
+        if ((phases & MLORA_PHASE_MAIN) && launch_main(a, main_blocks, s) != hipSuccess) return MLORA_EHIP;
     }
     return MLORA_OK;
 }
@@ -207,7 +224,7 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
 {
     return mlora_w4_layer_step_phases(projs, n_proj, xs, ys, row_adapter, M, y_dtype, workspace,
                                       workspace_bytes, stream,
-                                      MLORA_PHASE_SHRINK | MLORA_PHASE_BASE);
+                                      MLORA_PHASE_PRE | MLORA_PHASE_MAIN);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,

@@ -39,6 +39,10 @@ __host__ __device__ inline size_t blob_code_bytes(int K, int N) {
 __host__ __device__ inline size_t blob_scale_bytes(int K, int N, int group) {
     return (size_t)tiles_n(N) * (size_t)(K / group) * 128u;
 }
+// The kernels request whole batches of super-steps without clamping the last ones, so a wave
+// may read (and ignore) up to 3 super-steps of codes and as many groups of scales past the end
+// of its tile: the blob ends with slack that keeps those reads inside the allocation.
+constexpr size_t BLOB_SLACK_BYTES = 16384;
 __host__ __device__ inline int field_pos(int i) { return (3 + 4 * (i >> 1) + 16 * (i & 1)) & 31; }
 __host__ __device__ inline uint32_t rotl32(uint32_t v, int s) {
     s &= 31;
@@ -51,7 +55,7 @@ __host__ __device__ inline uint32_t rotr32(uint32_t v, int s) { return rotl32(v,
 // ---------------------------------------------------------------------------------------------
 constexpr int MAX_PROJ_PER_LAUNCH = 16;
 constexpr int ROWS_PER_BLOCK16 = 16;
-constexpr int MAX_KCHUNKS = 8;     // partial sums of the shrink step the epilogue adds up
+constexpr int MAX_KCHUNKS = 4;     // partial sums of the shrink step the epilogue adds up
 
 struct ProjArgs {
     const uint4 *codes;        // blob, code region
@@ -60,24 +64,32 @@ struct ProjArgs {
     void *y;                   // [M][N]
     const uint16_t *lora_a;    // bf16 [n_adapters][rank][K]
     const uint16_t *lora_b;    // bf16 [n_adapters][N][rank]
-    float *t_part;             // fp32 [kch][M][r16], written by the shrink kernel
+    float *t_part;             // fp32 [kch][M][r16], written by the shrink blocks
+    float *partial;            // fp32 [ksplit-1][tiles][m_pad][64], written by the split-K units
     int K, N;
     int spg;                   // k-steps per scale group (group / 32)
     int n_adapters, rank;
     int r16;                   // rank rounded up to a multiple of 16
     int kch;                   // number of K chunks of the shrink step
     float alpha;
-    int tile_begin;            // first block index of this projection in the base kernel
-    int shrink_begin;          // first block index of this projection in the shrink kernel
+    int ksplit;                // K units per tile; unit 0 finishes the tile, the others run ahead
 };
 
 struct LayerArgs {
+    // first block of each projection: in the main launch, among the split-K blocks of the pre
+    // launch, and among its shrink blocks (which follow all split-K blocks)
+    int main_begin[MAX_PROJ_PER_LAUNCH];
+    int pre_begin[MAX_PROJ_PER_LAUNCH];
+    int shrink_begin[MAX_PROJ_PER_LAUNCH];
     ProjArgs p[MAX_PROJ_PER_LAUNCH];
     const int *row_adapter;    // may be null
     int n_proj;
     int M;
     int y_fp32;
-    int max_row_tiles;         // upper bound of 16-row tiles of adapter segments
+    int m_pad;                 // M rounded up to whole row chunks of the base kernel
+    int pre_base_blocks;       // split-K blocks in the pre launch; shrink blocks follow them
+    uint32_t code_mask;        // 0x00780078: the two code fields of a bf16 pair
+    uint32_t code_bias;        // 0x41804180: sign, exponent and leading mantissa bit of 16.0
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -104,6 +116,21 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
 }
 
+// Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
+// library build); each wave appends (constant-rate clock, shader clock) pairs to a buffer.
+#ifdef MLORA_TRACE
+extern __device__ unsigned long long *g_trace;           // [n_waves][16]
+#define MLORA_TRACE_POINT(slot, id)                                                        \
+    do {                                                                                   \
+        if (g_trace && (threadIdx.x & 63) == 0) {                                          \
+            g_trace[(size_t)(slot) * 16 + 2 * (id)] = wall_clock64();                      \
+            g_trace[(size_t)(slot) * 16 + 2 * (id) + 1] = clock64();                       \
+        }                                                                                  \
+    } while (0)
+#else
+#define MLORA_TRACE_POINT(slot, id) do { } while (0)
+#endif
+
 // host launchers (each file defines its own)
 hipError_t launch_prepack(int K, int N, int group, const uint8_t *wq, const uint16_t *scales,
                           void *blob, hipStream_t s);
@@ -111,7 +138,12 @@ hipError_t launch_unpack(int K, int N, int group, const void *blob, int8_t *code
                          hipStream_t s);
 hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int *perm,
                              int *seg_adapter, int *seg_start, int *n_seg, hipStream_t s);
-hipError_t launch_shrink(const LayerArgs &a, int n_blocks, hipStream_t s);
-hipError_t launch_base(const LayerArgs &a, int n_tiles, hipStream_t s);
+// pre launch: split-K units 1.. of long-K projections plus the group + shrink blocks;
+// main launch: unit 0 of every tile, which also adds the partials and the LoRA term
+hipError_t launch_pre(const LayerArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_main(const LayerArgs &a, int n_blocks, hipStream_t s);
+
+constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
+__host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : 32; }
 
 }  // namespace mlora

@@ -1,0 +1,603 @@
+// The two launches of a layer step.
+//
+// Base product.  A block of four waves owns one K unit (at most 2048 inputs) of one tile of 64
+// output columns for one chunk of 16*MB rows.  Each wave issues ALL loads of its share up
+// front (packed codes straight from HBM with one 128-bit load per lane and k-step, the rows of
+// x and the fp16 scales from L2), then turns every code dword into four bf16 pairs with 7
+// integer ops and feeds 16x16x32 bf16 MFMAs whose A operand is the block of rows of x.
+// Scales multiply the fp32 result of each scale group, so codes enter the matrix unit exactly.
+// The four partial tiles are added in LDS in a fixed order.
+//
+// Projections with more than 2048 inputs are cut into several K units per tile: units 1.. run
+// in the pre launch and leave fp32 partial tiles in the workspace; unit 0 runs in the main
+// launch, adds them in order, adds the LoRA term alpha * B[a(m)][n] . t[m] and stores y.
+//
+// LoRA shrink (pre launch, next to the split-K units).  A block owns one (16-row tile of an
+// adapter segment, block of 16 ranks, K chunk): after grouping the rows in LDS its four waves
+// split the chunk, each accumulating a 16x16 tile with MFMA (A operand: rows of x, B operand:
+// 16 rows of A[adapter]); the sum goes to t_part[chunk][row][rank].
+#include "group_rows.hpp"
+
+namespace mlora {
+
+#ifdef MLORA_TRACE
+__device__ unsigned long long *g_trace = nullptr;
+extern "C" hipError_t mlora_trace_set(unsigned long long *p)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof p);
+}
+#endif
+
+// ------------------------------------------------------------------------------------------
+// base product
+// ------------------------------------------------------------------------------------------
+struct Stage {
+    uint4 w[4];
+    uint2 sc[4];
+};
+
+__device__ __forceinline__ float half_bits_lo(uint32_t v) { return half_bits_to_float((uint16_t)(v & 0xFFFFu)); }
+__device__ __forceinline__ float half_bits_hi(uint32_t v) { return half_bits_to_float((uint16_t)(v >> 16)); }
+
+// 8 packed codes -> 8 bf16 values code + 24 (4 dwords)
+__device__ __forceinline__ uint4 expand_codes(uint32_t w, uint32_t mask, uint32_t bias)
+{
+    uint4 o;
+    o.x = (w & mask) | bias;
+    o.y = (__builtin_amdgcn_alignbit(w, w, 4) & mask) | bias;
+    o.z = (__builtin_amdgcn_alignbit(w, w, 8) & mask) | bias;
+    o.w = (__builtin_amdgcn_alignbit(w, w, 12) & mask) | bias;
+    return o;
+}
+
+// One super-step (4 k-steps).  xs[mb] points at this lane's row of the wave's staged x, at the
+// first input of the super-step plus 8*(lane/16): the MFMA A fragment of k-step s is the
+// 16 bytes at xs[mb] + 64*s.
+template <int MB, int SPG>
+__device__ __forceinline__ void compute_stage(const Stage &st, const unsigned char *const (&xs)[MB],
+                                     f32x4 (&acc)[MB][4], uint32_t mask, uint32_t bias)
+{
+    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
+    uint4 xf[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) xf[mb][s] = *reinterpret_cast<const uint4 *>(xs[mb] + 64 * s);
+#pragma unroll
+    for (int gi = 0; gi < 4 / SPG; ++gi) {
+        // -24 * sum of x over the group's inputs: cancels the offset of the stored codes
+        f32x4 corr[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < SPG; ++s) corr[mb] = mfma16(xf[mb][gi * SPG + s], neg24, corr[mb]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x4 d[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) d[mb] = corr[mb];
+#pragma unroll
+            for (int s = 0; s < SPG; ++s) {
+                const uint4 wv = st.w[gi * SPG + s];
+                const uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
+                const uint4 wb = expand_codes(wj, mask, bias);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) d[mb] = mfma16(xf[mb][gi * SPG + s], wb, d[mb]);
+            }
+            const uint2 sv = st.sc[gi];
+            const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
+                           : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][e], sj, acc[mb][j][e]);
+        }
+    }
+}
+
+// Weight and scale loads are unconditional: a load behind a branch would make the compiler
+// wait for every outstanding load before the first use, because it could no longer count the
+// loads issued after it.  ss is a compile-time constant at every call: the addresses are a
+// base plus an immediate.
+template <int SPG>
+__device__ __forceinline__ void load_stage(Stage &st, const uint4 *wp, const uint2 *sp, int ss)
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s) st.w[s] = wp[(ss * 4 + s) * 64];
+#pragma unroll
+    for (int gi = 0; gi < 4 / SPG; ++gi) st.sc[gi] = sp[(ss * (4 / SPG) + gi) * 16];
+}
+
+// Rows of x for one batch of this wave's inputs go through a wave-private LDS buffer: every
+// row segment is read from global memory once, fully coalesced (a wave-wide load covers 1 KiB
+// of consecutive segment bytes), and the MFMA fragments are then read back with ds_read_b128.
+// XROW = bytes per staged row; the 16 bytes of padding put consecutive rows 4 banks apart,
+// which makes the fragment reads conflict-free.
+template <int XR, int BATCH>
+struct XStage {
+    static constexpr int ROWS = XR;                             // rows staged (a multiple of 8)
+    static constexpr int SEG = BATCH * SUPER_K * 2;             // bytes of one row in one batch
+    static constexpr int XROW = SEG + 16;
+    static constexpr int NLOAD = ROWS * SEG / 1024;             // wave-wide loads for all rows
+    static constexpr int BYTES = ROWS * XROW;                   // per wave
+};
+
+// loads [first, first + n) of the staging sequence; load i, lane l covers bytes
+// i*1024 + 16*l .. +15 of the (row-major) segment array
+// (a native vector type: copies of HIP's uint4 struct from global to LDS would be lowered to
+// memcpy through a private array instead of a register)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int XR, int BATCH, int N>
+__device__ __forceinline__ void stage_x_issue(u32x4 (&tmp)[N], int first, const uint16_t *x, int K, int m0,
+                                     int rows_here, int k0, int lane)
+{
+    using XS = XStage<XR, BATCH>;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int byte = (first + i) * 1024 + lane * 16;
+        const int row = min(byte / XS::SEG, rows_here - 1);
+        const int k = min(k0 + (byte % XS::SEG) / 2, K - 8);     // past the end: a valid duplicate
+        tmp[i] = *reinterpret_cast<const u32x4 *>(x + (size_t)(m0 + row) * K + k);
+    }
+}
+
+template <int XR, int BATCH, int N>
+__device__ __forceinline__ void stage_x_store(const u32x4 (&tmp)[N], int first, unsigned char *xbuf, int lane)
+{
+    using XS = XStage<XR, BATCH>;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int byte = (first + i) * 1024 + lane * 16;
+        *reinterpret_cast<u32x4 *>(xbuf + (byte / XS::SEG) * XS::XROW + byte % XS::SEG) = tmp[i];
+    }
+}
+
+// One batch: BATCH super-steps (BATCH * 4 KiB of codes per wave) are requested before the
+// first is used.  Order: rows of x (the oldest loads, they come from L2), all weight and scale
+// loads, x into LDS as soon as it has arrived, then the math as the weights arrive.  A batch
+// that reaches past count re-reads the last super-step and skips its math.  PREFETCH: after
+// the first super-step the loads the epilogue will need are issued (unconditionally, so that
+// the waits of the remaining super-steps can still be counted).
+template <int MB, int XR, int SPG, int BATCH, bool PREFETCH, class Prefetch>
+__device__ __forceinline__ void stream_batch(f32x4 (&acc)[MB][4], const uint4 *wp, const uint16_t *x, int K,
+                                    int m0, int rows_here, int k_first, const uint2 *sp, int b0,
+                                    int count, unsigned char *xbuf, uint32_t mask, uint32_t bias,
+                                    Prefetch &prefetch, [[maybe_unused]] int trace_slot)
+{
+    using XS = XStage<XR, BATCH>;
+    const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+    const int k0 = k_first + b0 * SUPER_K;
+    // super-steps past count are requested too (never used): the blob's slack keeps them in bounds
+    const uint4 *wpb = wp + (size_t)b0 * 256;
+    const uint2 *spb = sp + (size_t)b0 * (4 / SPG) * 16;
+    u32x4 xt[XS::NLOAD];
+    stage_x_issue<XR, BATCH>(xt, 0, x, K, m0, rows_here, k0, lane);
+    Stage st[BATCH];
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) load_stage<SPG>(st[i], wpb, spb, i);
+    stage_x_store<XR, BATCH>(xt, 0, xbuf, lane);
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+        const unsigned char *xs[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            xs[mb] = xbuf + min(mb * 16 + l16, rows_here - 1) * XS::XROW + 16 * lq + i * (SUPER_K * 2);
+        if (b0 + i < count) compute_stage<MB, SPG>(st[i], xs, acc, mask, bias);
+        if (i == 0) {
+            MLORA_TRACE_POINT(trace_slot, 6);
+            if (PREFETCH) prefetch.issue();
+        }
+    }
+}
+
+template <int MB, int XR, int SPG, int BATCH, class Prefetch>
+__device__ __forceinline__ void stream_k(f32x4 (&acc)[MB][4], const uint4 *wp, const uint16_t *x, int K,
+                                int m0, int rows_here, int k_first, const uint2 *sp, int count,
+                                unsigned char *xbuf, uint32_t mask, uint32_t bias,
+                                Prefetch &prefetch, int trace_slot)
+{
+    const int last = max(count, 1) - 1;
+    int b0 = 0;
+    for (; b0 + BATCH <= last; b0 += BATCH)
+        stream_batch<MB, XR, SPG, BATCH, false>(acc, wp, x, K, m0, rows_here, k_first, sp, b0, count,
+                                            xbuf, mask, bias, prefetch, trace_slot);
+    stream_batch<MB, XR, SPG, BATCH, true>(acc, wp, x, K, m0, rows_here, k_first, sp, b0, count, xbuf,
+                                       mask, bias, prefetch, trace_slot);
+}
+
+// Loads the epilogue needs, issued from inside the K loop (all unconditional; a thread with
+// nothing to fetch re-reads a valid address).
+template <int N>
+struct EpiPrefetch {
+    const uint16_t *brow[N > 0 ? N : 1];     // row of B per output (or a safe address)
+    int bstep[N > 0 ? N : 1];                // rank - 8 (offset of the last 8 ranks), or 0
+    const float *tp;                         // this thread's entry of t_part[0] (or a safe address)
+    size_t tstride;                          // distance between K chunks of t_part
+    int kch, t_ml, t_jj;
+    bool t_mine;
+    uint4 b[N > 0 ? N : 1][2];
+    float t[MAX_KCHUNKS];
+    __device__ __forceinline__ void issue()
+    {
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            b[q][0] = *reinterpret_cast<const uint4 *>(brow[q]);
+            b[q][1] = *reinterpret_cast<const uint4 *>(brow[q] + min(8, bstep[q]));
+        }
+        if (N > 0) {
+#pragma unroll
+            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) t[kc] = tp[(size_t)min(kc, kch - 1) * tstride];
+        }
+    }
+};
+
+constexpr int FAST_RANK = 16;                  // the epilogue prefetch covers ranks up to this
+
+// LDS of a base block: the per-wave x staging buffers, reused after the K loop for the
+// per-wave partial tiles, followed by alpha * t of the chunk's rows.
+template <int MB, int XR, int WAVES, int BATCH>
+struct BaseLds {
+    static constexpr int X_BYTES = WAVES * XStage<XR, BATCH>::BYTES;
+    static constexpr int RED_BYTES = WAVES * MB * 1024 * 4;
+    static constexpr int FRONT = X_BYTES > RED_BYTES ? X_BYTES : RED_BYTES;
+    static constexpr int TS_STRIDE = MLORA_MAX_RANK + 4;
+    static constexpr int BYTES = FRONT + 16 * MB * TS_STRIDE * 4;
+    unsigned char *base;
+    __device__ unsigned char *xbuf(int wave) const { return base + wave * XStage<XR, BATCH>::BYTES; }
+    __device__ float *red(int wave) const { return reinterpret_cast<float *>(base) + wave * MB * 1024; }
+    __device__ float *t_row(int ml) const { return reinterpret_cast<float *>(base + FRONT) + ml * TS_STRIDE; }
+};
+
+__device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
+{
+    l = fmaf(bf16_bits_to_float(b8.x & 0xFFFFu), t[0], l);
+    l = fmaf(bf16_bits_to_float(b8.x >> 16), t[1], l);
+    l = fmaf(bf16_bits_to_float(b8.y & 0xFFFFu), t[2], l);
+    l = fmaf(bf16_bits_to_float(b8.y >> 16), t[3], l);
+    l = fmaf(bf16_bits_to_float(b8.z & 0xFFFFu), t[4], l);
+    l = fmaf(bf16_bits_to_float(b8.z >> 16), t[5], l);
+    l = fmaf(bf16_bits_to_float(b8.w & 0xFFFFu), t[6], l);
+    l = fmaf(bf16_bits_to_float(b8.w >> 16), t[7], l);
+    return l;
+}
+
+// ku == 0: finish the tile (add split-K partials, LoRA term, store y); ku > 0: leave a partial.
+// WAVES waves split the unit's super-steps; thread (wave w, lane l) then finishes the EPT tile
+// elements i = w*EPT .. +EPT-1, element i = (mb, j, e) being row 16*mb + 4*(l/16) + e, column
+// 16*j + l%16 (the MFMA result layout).
+template <int MB, int XR, int WAVES, int BATCH>
+__device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int tile, int ku, int m0,
+                                 const BaseLds<MB, XR, WAVES, BATCH> &lds)
+{
+    constexpr int ROWS = 16 * MB;
+    constexpr int NT = 64 * WAVES;
+    constexpr int EPT = MB * 16 / WAVES;
+    const int K = P.K, N = P.N, M = a.M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * WAVES + wave;
+    MLORA_TRACE_POINT(trace_slot, 0);
+
+    // super-steps of this K unit, then of this wave (balanced splits)
+    const int nss = K / SUPER_K;
+    const int uq = nss / P.ksplit, ur = nss % P.ksplit;
+    const int unit_beg = ku * uq + min(ku, ur), unit_cnt = uq + (ku < ur ? 1 : 0);
+    const int q = unit_cnt / WAVES, r = unit_cnt % WAVES;
+    const int my_cnt = q + (wave < r ? 1 : 0);
+    // a wave without work still issues (valid) loads: point it at the unit's first super-step
+    const int my_beg = my_cnt > 0 ? unit_beg + wave * q + min(wave, r) : unit_beg;
+
+    const int ksteps = K / KSTEP;
+    const int ngroups = ksteps / P.spg;
+    const uint4 *wp = P.codes + ((size_t)tile * ksteps + (size_t)my_beg * 4) * 64 + lane;
+    const uint2 *sp = P.scales + ((size_t)tile * ngroups + (size_t)my_beg * (4 / P.spg)) * 16 + l16;
+
+    // what this thread will finish, and the adapter of each of its rows
+    const bool lora = (ku == 0) && (a.row_adapter != nullptr) && (P.n_adapters > 0);
+    const int rows_here = min(ROWS, M - m0);
+    constexpr bool PREFETCH = EPT <= 4;                    // more outputs per thread: too many registers
+    const bool fast = PREFETCH && lora && P.rank <= FAST_RANK && rows_here * P.r16 <= NT;
+    const int *ra_safe = lora ? a.row_adapter : reinterpret_cast<const int *>(P.codes);
+    int out_ml[EPT], out_col[EPT], out_ad[EPT];
+    const int ra_last = lora ? M - 1 : 0;                  // unconditional loads, decoded below
+#pragma unroll
+    for (int qq = 0; qq < EPT; ++qq) {
+        const int i = wave * EPT + qq;
+        out_ml[qq] = (i >> 4) * 16 + 4 * lq + (i & 3);
+        out_col[qq] = 16 * ((i >> 2) & 3) + l16;
+        out_ad[qq] = ra_safe[min(m0 + out_ml[qq], ra_last)];
+    }
+#pragma unroll
+    for (int qq = 0; qq < EPT; ++qq) {
+        const int v = out_ad[qq];
+        out_ad[qq] = (lora && m0 + out_ml[qq] < M && v >= 0 && v < P.n_adapters) ? v : -1;
+    }
+
+    f32x4 acc[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    MLORA_TRACE_POINT(trace_slot, 1);
+
+    // epilogue operands fetched while the last super-steps are still being computed: the rows
+    // of B of this thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
+    EpiPrefetch<PREFETCH ? EPT : 0> pf;
+    pf.t_ml = tid / max(P.r16, 1);
+    pf.t_jj = tid % max(P.r16, 1);
+    pf.t_mine = fast && tid < rows_here * P.r16;
+    {
+        const uint16_t *safe = reinterpret_cast<const uint16_t *>(P.codes);
+#pragma unroll
+        for (int qq = 0; qq < (PREFETCH ? EPT : 0); ++qq) {
+            const int n = tile * TILE_N + out_col[qq];
+            const bool ok = fast && out_ad[qq] >= 0 && n < N;
+            pf.brow[qq] = ok ? P.lora_b + ((size_t)out_ad[qq] * N + n) * P.rank : safe;
+            pf.bstep[qq] = ok ? P.rank - 8 : 0;
+        }
+        pf.tp = pf.t_mine ? P.t_part + (size_t)(m0 + pf.t_ml) * P.r16 + pf.t_jj
+                          : reinterpret_cast<const float *>(P.codes);
+        pf.tstride = pf.t_mine ? (size_t)M * P.r16 : 0;
+        pf.kch = P.kch;
+    }
+
+    // the two constants of expand_codes arrive as kernel arguments so that they live in
+    // registers and each field pair costs one and-or instead of an and plus an or with literals
+    const uint32_t mask = a.code_mask;
+    uint32_t bias = a.code_bias;
+    asm volatile("" : "+v"(bias));      // pin to a vector register (one scalar operand per op)
+    unsigned char *xbuf = lds.xbuf(wave);
+    const int k_first = my_beg * SUPER_K;
+    if (P.spg == 1)      stream_k<MB, XR, 1, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
+    else if (P.spg == 2) stream_k<MB, XR, 2, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
+    else                 stream_k<MB, XR, 4, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
+
+    MLORA_TRACE_POINT(trace_slot, 2);
+    // partial tiles -> LDS (over the staging buffers, once every wave is done reading them)
+    __syncthreads();
+    {
+        float *red = lds.red(wave);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) red[((mb * 4 + j) * 4 + e) * 64 + lane] = acc[mb][j][e];
+    }
+
+    // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
+    if (fast) {
+        if constexpr (PREFETCH) {
+            if (pf.t_mine) {
+                float v = 0.f;
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? pf.t[kc] : 0.f;
+                lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
+            }
+        }
+    } else if (lora) {
+        for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
+            const int ml = idx / P.r16, jj = idx % P.r16;
+            const int ad = a.row_adapter[m0 + ml];
+            float v = 0.f;
+            if (ad >= 0 && ad < P.n_adapters)
+                for (int kc = 0; kc < P.kch; ++kc)
+                    v += P.t_part[((size_t)kc * M + (m0 + ml)) * P.r16 + jj];
+            lds.t_row(ml)[jj] = v * P.alpha;
+        }
+    }
+    MLORA_TRACE_POINT(trace_slot, 3);
+    __syncthreads();
+    MLORA_TRACE_POINT(trace_slot, 4);
+
+    const int tiles = tiles_n(N);
+#pragma unroll
+    for (int qq = 0; qq < EPT; ++qq) {
+        const int i = wave * EPT + qq;
+        const int off = i * 64 + lane;
+        float v = lds.red(0)[off];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) v += lds.red(w)[off];
+        if (qq == 0) MLORA_TRACE_POINT(trace_slot, 7);
+        const int ml = out_ml[qq], col = out_col[qq];
+        const int m = m0 + ml;
+        const int n = tile * TILE_N + col;
+        if (ku > 0) {
+            P.partial[(((size_t)(ku - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col] = v;
+            continue;
+        }
+        if (m < M && n < N) {
+            for (int u = 1; u < P.ksplit; ++u)
+                v += P.partial[(((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col];
+            const int ad = out_ad[qq];
+            if (ad >= 0) {
+                float l = 0.f;
+                if (fast) {
+                    if constexpr (PREFETCH) {
+                        l = dot8(pf.b[qq][0], lds.t_row(ml), l);
+                        if (P.rank > 8) l = dot8(pf.b[qq][1], lds.t_row(ml) + 8, l);
+                    }
+                } else {
+                    const uint16_t *brow = P.lora_b + ((size_t)ad * N + n) * P.rank;
+                    for (int jj = 0; jj < P.rank; jj += 8)
+                        l = dot8(*reinterpret_cast<const uint4 *>(brow + jj), lds.t_row(ml) + jj, l);
+                }
+                v += l;
+            }
+            if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
+            else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
+        }
+    }
+    MLORA_TRACE_POINT(trace_slot, 5);
+}
+
+// ------------------------------------------------------------------------------------------
+// LoRA shrink
+// ------------------------------------------------------------------------------------------
+struct ShrinkLds {
+    GroupLds g;
+    float red[4][256];
+};
+
+__device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int local, ShrinkLds &lds)
+{
+    GroupLds &g = lds.g;
+    const int jblocks = P.r16 / 16;
+    const int kc = local % P.kch;
+    const int jb = (local / P.kch) % jblocks;
+    const int ti = local / (P.kch * jblocks);
+
+    group_rows_lds(a.row_adapter, a.M, P.n_adapters, g);
+
+    // locate row tile ti among the segments (16 rows per tile, tiles never straddle segments)
+    int seg = -1, first = 0, tiles_before = 0;
+    for (int s = 0; s < g.n_seg; ++s) {
+        const int len = (int)g.seg_start[s + 1] - (int)g.seg_start[s];
+        const int nt = (len + 15) / 16;
+        if (ti < tiles_before + nt) {
+            seg = s;
+            first = (int)g.seg_start[s] + 16 * (ti - tiles_before);
+            break;
+        }
+        tiles_before += nt;
+    }
+    if (seg < 0) return;                                   // uniform over the block
+    const int adapter = g.seg_adapter[seg];
+    const int rows_here = min(16, (int)g.seg_start[seg + 1] - first);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // k-steps of this block, then of this wave (balanced splits)
+    const int nks = P.K / KSTEP;
+    const int q = nks / P.kch, r = nks % P.kch;
+    const int blk_beg = kc * q + min(kc, r), blk_cnt = q + (kc < r ? 1 : 0);
+    const int wq_ = blk_cnt / 4, wr = blk_cnt % 4;
+    const int my_beg = blk_beg + (wave & 3) * wq_ + min(wave & 3, wr), my_cnt = wq_ + ((wave & 3) < wr ? 1 : 0);
+
+    const int row = (l16 < rows_here) ? (int)g.perm[first + l16] : -1;
+    const int j = jb * 16 + l16;
+    const bool j_ok = j < P.rank;
+    const uint16_t *xp = P.x + (size_t)(row < 0 ? 0 : row) * P.K + 8 * lq + (size_t)my_beg * KSTEP;
+    const uint16_t *ap = P.lora_a + ((size_t)adapter * P.rank + (j_ok ? j : 0)) * P.K + 8 * lq +
+                         (size_t)my_beg * KSTEP;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    if (wave >= 4) s = my_cnt;                              // blocks may be wider than 4 waves
+    for (; s + 4 <= my_cnt; s += 4) {
+        uint4 xa[4], ab[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            xa[u] = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)(s + u) * KSTEP) : zero;
+            ab[u] = j_ok ? *reinterpret_cast<const uint4 *>(ap + (size_t)(s + u) * KSTEP) : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma16(xa[u], ab[u], acc);
+    }
+    for (; s < my_cnt; ++s) {
+        const uint4 xa = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)s * KSTEP) : zero;
+        const uint4 ab = j_ok ? *reinterpret_cast<const uint4 *>(ap + (size_t)s * KSTEP) : zero;
+        acc = mfma16(xa, ab, acc);
+    }
+    if (wave < 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lds.red[wave][e * 64 + lane] = acc[e];
+    }
+    __syncthreads();
+    if (wave < 4) {
+        // thread (e, lane) owns tile row 4*(lane/16) + e and rank column lane%16
+        const int e = wave;
+        const int i = 4 * lq + e;
+        const float v = ((lds.red[0][e * 64 + lane] + lds.red[1][e * 64 + lane]) +
+                         lds.red[2][e * 64 + lane]) + lds.red[3][e * 64 + lane];
+        if (i < rows_here) {
+            const int m = g.perm[first + i];
+            P.t_part[((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// kernels
+// ------------------------------------------------------------------------------------------
+// MB blocks of 16 rows per chunk, XR rows staged in LDS (the smallest multiple of 8 that holds
+// the rows of a chunk decides which instance runs): 4 waves per block; up to 16 rows a wave
+// keeps 4 super-steps (16 KiB of codes) in flight, above that 2.
+template <int MB> struct Shape;
+template <> struct Shape<1> { static constexpr int WAVES = 4, BATCH = 4, OCC = 2; };
+template <> struct Shape<2> { static constexpr int WAVES = 4, BATCH = 2, OCC = 2; };
+
+template <int MB, int XR>
+using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>;
+template <int MB, int XR>
+constexpr int pre_lds_bytes()
+{
+    return BaseLdsOf<MB, XR>::BYTES > (int)sizeof(ShrinkLds) ? BaseLdsOf<MB, XR>::BYTES : (int)sizeof(ShrinkLds);
+}
+
+__device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH], int n_proj, int b)
+{
+    int pi = 0;
+    for (int i = 1; i < n_proj; ++i)
+        if (b >= begin[i]) pi = i;
+    return pi;
+}
+
+template <int MB, int XR>
+__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_pre_kernel(const LayerArgs a)
+{
+    __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
+    const int b = (int)blockIdx.x;
+    if (b < a.pre_base_blocks) {
+        const BaseLdsOf<MB, XR> lds{smem};
+        const int pi = find_proj(a.pre_begin, a.n_proj, b);
+        const ProjArgs &P = a.p[pi];
+        const int local = b - a.pre_begin[pi];
+        const int tiles = tiles_n(P.N);
+        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>(a, P, local % tiles, 1 + local / tiles,
+                                                              (int)blockIdx.y * 16 * MB, lds);
+    } else {
+        if (blockIdx.y != 0) return;
+        const int sb = b - a.pre_base_blocks;
+        const int pi = find_proj(a.shrink_begin, a.n_proj, sb);
+        shrink_block(a, a.p[pi], sb - a.shrink_begin[pi], *reinterpret_cast<ShrinkLds *>(smem));
+    }
+}
+
+template <int MB, int XR>
+__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_main_kernel(const LayerArgs a)
+{
+    __shared__ __align__(16) unsigned char smem[BaseLdsOf<MB, XR>::BYTES];
+    const BaseLdsOf<MB, XR> lds{smem};
+    const int b = (int)blockIdx.x;
+    const int pi = find_proj(a.main_begin, a.n_proj, b);
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>(a, a.p[pi], b - a.main_begin[pi], 0,
+                                                          (int)blockIdx.y * 16 * MB, lds);
+}
+
+template <int MB, int XR>
+static hipError_t launch_both(const LayerArgs &a, int n_blocks, bool pre, hipStream_t s)
+{
+    const dim3 grid((unsigned)n_blocks, (unsigned)(a.m_pad / rows_per_chunk(a.M)));
+    const dim3 block(64 * Shape<MB>::WAVES);
+    if (pre) layer_pre_kernel<MB, XR><<<grid, block, 0, s>>>(a);
+    else     layer_main_kernel<MB, XR><<<grid, block, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+static hipError_t launch_layer(const LayerArgs &a, int n_blocks, bool pre, hipStream_t s)
+{
+    if (a.M <= 8)  return launch_both<1, 8>(a, n_blocks, pre, s);
+    if (a.M <= 16) return launch_both<1, 16>(a, n_blocks, pre, s);
+    if (a.M <= 24) return launch_both<2, 24>(a, n_blocks, pre, s);
+    return launch_both<2, 32>(a, n_blocks, pre, s);
+}
+
+hipError_t launch_pre(const LayerArgs &a, int n_blocks, hipStream_t s) { return launch_layer(a, n_blocks, true, s); }
+hipError_t launch_main(const LayerArgs &a, int n_blocks, hipStream_t s) { return launch_layer(a, n_blocks, false, s); }
+
+}  // namespace mlora

@@ -35,10 +35,11 @@ def test_strerror_covers_all_codes():
 
 
 def test_blob_bytes():
-    # codes: ceil(N/64) tiles x K/32 steps x 1 KiB; scales: tiles x K/group x 128 B
-    assert lib.blob_bytes(256, 256, 32) == 4 * 8 * 1024 + 4 * 8 * 128
-    assert lib.blob_bytes(256, 200, 64) == 4 * 8 * 1024 + 4 * 4 * 128
-    assert lib.blob_bytes(2048, 8192, 32) == 8192 * 2048 // 2 + 8192 * 64 * 2
+    # codes: ceil(N/64) tiles x K/32 steps x 1 KiB; scales: tiles x K/group x 128 B; 16 KiB slack
+    slack = 16384
+    assert lib.blob_bytes(256, 256, 32) == 4 * 8 * 1024 + 4 * 8 * 128 + slack
+    assert lib.blob_bytes(256, 200, 64) == 4 * 8 * 1024 + 4 * 4 * 128 + slack
+    assert lib.blob_bytes(2048, 8192, 32) == 8192 * 2048 // 2 + 8192 * 64 * 2 + slack
     for bad in [(100, 64, 32), (256, 64, 16), (256, 0, 32), (0, 64, 32), (64, 64, 32)]:
         assert lib.blob_bytes(*bad) == 0
 
@@ -54,8 +55,11 @@ def test_workspace_bytes():
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 4 * 8 * 16 * 4
     p = proj(K=256, rank=8)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == 256
+    # K = 16384 = 8 units of 2048 inputs: 7 fp32 partial tiles [m_pad = 64][64] per tile of columns
     p = proj(K=16384, rank=64)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == 8 * 64 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == 4 * 64 * 64 * 4 + 7 * 1 * 64 * 64 * 4
+    p = proj(K=4096, N=200, n_ad=0, rank=0, a=None, b=None)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == 1 * 4 * 16 * 64 * 4
     p = proj(n_ad=0, rank=0, a=None, b=None)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 0
 
