@@ -31,11 +31,6 @@ extern "C" hipError_t mlora_trace_set(unsigned long long *p)
 // ------------------------------------------------------------------------------------------
 // base product
 // ------------------------------------------------------------------------------------------
-struct Stage {
-    uint4 w[4];
-    uint2 sc[4];
-};
-
 __device__ __forceinline__ float half_bits_lo(uint32_t v) { return half_bits_to_float((uint16_t)(v & 0xFFFFu)); }
 __device__ __forceinline__ float half_bits_hi(uint32_t v) { return half_bits_to_float((uint16_t)(v >> 16)); }
 
@@ -50,162 +45,139 @@ __device__ __forceinline__ uint4 expand_codes(uint32_t w, uint32_t mask, uint32_
     return o;
 }
 
-// One super-step (4 k-steps).  xs[mb] points at this lane's row of the wave's staged x, at the
-// first input of the super-step plus 8*(lane/16): the MFMA A fragment of k-step s is the
-// 16 bytes at xs[mb] + 64*s.
-template <int MB, int SPG>
-__device__ __forceinline__ void compute_stage(const Stage &st, const unsigned char *const (&xs)[MB],
-                                     f32x4 (&acc)[MB][4], uint32_t mask, uint32_t bias)
+// (a native vector type: copies of HIP's uint4 struct from global to LDS would be lowered to
+// memcpy through a private array instead of going through registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// A wave works through its inputs in rounds of R k-steps.  All operands of a round (R KiB of
+// packed codes, the rows of x, the scales) are staged in a wave-private LDS buffer, and the
+// math of a round is a ROLLED loop over its scale groups that reads everything back from
+// LDS.  The loop is the point of the design: code that runs once is fetched at about 10
+// cycles per instruction (instruction-cache misses), a loop body only on its first pass.
+//
+// Rounds come in pairs: the loads of both rounds of a pair are issued into two register sets
+// before anything is waited for, so a wave keeps 2*R KiB of codes in flight; set A is written
+// to LDS and computed while set B is still arriving.
+// ------------------------------------------------------------------------------------------
+template <int XR, int R>
+struct RoundLds {
+    static constexpr int W_BYTES = R * 1024;
+    static constexpr int SEG = R * 64;                         // bytes of one row of x in a round
+    static constexpr int XROW = SEG + 16;                      // +16: rows 4 banks apart
+    static constexpr int X_BYTES = XR * XROW;
+    static constexpr int SC_BYTES = 1024;                      // up to 8 groups x 128 bytes
+    static constexpr int NXL = XR * SEG / 1024;                // wave-wide loads for the rows of x
+    static constexpr int BYTES = W_BYTES + X_BYTES + SC_BYTES; // per wave
+};
+
+template <int XR, int R>
+struct RoundRegs {
+    u32x4 w[R];                                  // packed codes: from HBM, requested first
+    u32x4 x[RoundLds<XR, R>::NXL];               // rows of x and the scales: small, from L2
+    u32x4 sc;
+};
+
+// Request the codes of one round: k-steps [ks, ks + R) of the tile.  Weight and scale
+// addresses are not clamped (the blob's slack keeps reads past the end in bounds).
+template <int XR, int R>
+__device__ __forceinline__ void round_issue_w(RoundRegs<XR, R> &rr, const uint4 *codes_tile, int ks, int lane)
 {
+    const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (size_t)ks * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < R; ++i) rr.w[i] = wp[i * 64];
+}
+
+// Request the rows of x (clamped to the row) and the scales of one round.
+template <int XR, int R>
+__device__ __forceinline__ void round_issue_xs(RoundRegs<XR, R> &rr, const uint2 *scales_tile, int spg,
+                                               const uint16_t *x, int K, int m0, int rows_here,
+                                               int ks, int lane)
+{
+    using L = RoundLds<XR, R>;
+#pragma unroll
+    for (int i = 0; i < L::NXL; ++i) {
+        const int byte = i * 1024 + lane * 16;
+        const int row = min(byte / L::SEG, rows_here - 1);
+        const int k = min(ks * KSTEP + (byte % L::SEG) / 2, K - 8);
+        rr.x[i] = *reinterpret_cast<const u32x4 *>(x + (size_t)(m0 + row) * K + k);
+    }
+    // the round's groups are contiguous: 128 bytes each, lane l takes bytes 16*l..
+    rr.sc = *(reinterpret_cast<const u32x4 *>(scales_tile + (size_t)(ks / spg) * 16) + lane);
+}
+
+template <int XR, int R>
+__device__ __forceinline__ void round_to_lds(const RoundRegs<XR, R> &rr, unsigned char *buf, int lane)
+{
+    using L = RoundLds<XR, R>;
+#pragma unroll
+    for (int i = 0; i < R; ++i) *reinterpret_cast<u32x4 *>(buf + i * 1024 + lane * 16) = rr.w[i];
+#pragma unroll
+    for (int i = 0; i < L::NXL; ++i) {
+        const int byte = i * 1024 + lane * 16;
+        *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + (byte / L::SEG) * L::XROW + byte % L::SEG) = rr.x[i];
+    }
+    *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + L::X_BYTES + lane * 16) = rr.sc;
+}
+
+// Math of one round: n_steps (a multiple of 4) k-steps starting at the front of the buffer.
+// One loop pass = one scale group = SPG k-steps.
+template <int MB, int XR, int R, int SPG>
+__device__ __forceinline__ void round_compute(f32x4 (&acc)[MB][4], const unsigned char *buf,
+                                              int n_steps, int rows_here, uint32_t mask,
+                                              uint32_t bias, int lane)
+{
+    using L = RoundLds<XR, R>;
+    const int l16 = lane & 15, lq = lane >> 4;
     const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
-    uint4 xf[MB][4];
+    const unsigned char *wl = buf + lane * 16;
+    const unsigned char *xl[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
+        xl[mb] = buf + L::W_BYTES + min(mb * 16 + l16, rows_here - 1) * L::XROW + 16 * lq;
+    const unsigned char *sl = buf + L::W_BYTES + L::X_BYTES + l16 * 8;
+#pragma nounroll
+    for (int g = 0; g < n_steps / SPG; ++g) {
+        uint4 xf[MB][SPG], wf[SPG];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) xf[mb][s] = *reinterpret_cast<const uint4 *>(xs[mb] + 64 * s);
+        for (int s = 0; s < SPG; ++s) {
+            wf[s] = *reinterpret_cast<const uint4 *>(wl + (g * SPG + s) * 1024);
 #pragma unroll
-    for (int gi = 0; gi < 4 / SPG; ++gi) {
+            for (int mb = 0; mb < MB; ++mb)
+                xf[mb][s] = *reinterpret_cast<const uint4 *>(xl[mb] + (g * SPG + s) * 64);
+        }
+        const uint2 sv = *reinterpret_cast<const uint2 *>(sl + g * 128);
         // -24 * sum of x over the group's inputs: cancels the offset of the stored codes
         f32x4 corr[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < SPG; ++s) corr[mb] = mfma16(xf[mb][gi * SPG + s], neg24, corr[mb]);
+            for (int s = 0; s < SPG; ++s) corr[mb] = mfma16(xf[mb][s], neg24, corr[mb]);
+        }
+        f32x4 d[MB][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) d[mb][j] = corr[mb];
+#pragma unroll
+            for (int s = 0; s < SPG; ++s) {
+                const uint32_t wj = j == 0 ? wf[s].x : j == 1 ? wf[s].y : j == 2 ? wf[s].z : wf[s].w;
+                const uint4 wb = expand_codes(wj, mask, bias);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) d[mb][j] = mfma16(xf[mb][s], wb, d[mb][j]);
+            }
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            f32x4 d[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) d[mb] = corr[mb];
-#pragma unroll
-            for (int s = 0; s < SPG; ++s) {
-                const uint4 wv = st.w[gi * SPG + s];
-                const uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
-                const uint4 wb = expand_codes(wj, mask, bias);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) d[mb] = mfma16(xf[mb][gi * SPG + s], wb, d[mb]);
-            }
-            const uint2 sv = st.sc[gi];
             const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
                            : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][e], sj, acc[mb][j][e]);
+                for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][j][e], sj, acc[mb][j][e]);
         }
     }
-}
-
-// Weight and scale loads are unconditional: a load behind a branch would make the compiler
-// wait for every outstanding load before the first use, because it could no longer count the
-// loads issued after it.  ss is a compile-time constant at every call: the addresses are a
-// base plus an immediate.
-template <int SPG>
-__device__ __forceinline__ void load_stage(Stage &st, const uint4 *wp, const uint2 *sp, int ss)
-{
-#pragma unroll
-    for (int s = 0; s < 4; ++s) st.w[s] = wp[(ss * 4 + s) * 64];
-#pragma unroll
-    for (int gi = 0; gi < 4 / SPG; ++gi) st.sc[gi] = sp[(ss * (4 / SPG) + gi) * 16];
-}
-
-// Rows of x for one batch of this wave's inputs go through a wave-private LDS buffer: every
-// row segment is read from global memory once, fully coalesced (a wave-wide load covers 1 KiB
-// of consecutive segment bytes), and the MFMA fragments are then read back with ds_read_b128.
-// XROW = bytes per staged row; the 16 bytes of padding put consecutive rows 4 banks apart,
-// which makes the fragment reads conflict-free.
-template <int XR, int BATCH>
-struct XStage {
-    static constexpr int ROWS = XR;                             // rows staged (a multiple of 8)
-    static constexpr int SEG = BATCH * SUPER_K * 2;             // bytes of one row in one batch
-    static constexpr int XROW = SEG + 16;
-    static constexpr int NLOAD = ROWS * SEG / 1024;             // wave-wide loads for all rows
-    static constexpr int BYTES = ROWS * XROW;                   // per wave
-};
-
-// loads [first, first + n) of the staging sequence; load i, lane l covers bytes
-// i*1024 + 16*l .. +15 of the (row-major) segment array
-// (a native vector type: copies of HIP's uint4 struct from global to LDS would be lowered to
-// memcpy through a private array instead of a register)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-template <int XR, int BATCH, int N>
-__device__ __forceinline__ void stage_x_issue(u32x4 (&tmp)[N], int first, const uint16_t *x, int K, int m0,
-                                     int rows_here, int k0, int lane)
-{
-    using XS = XStage<XR, BATCH>;
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int byte = (first + i) * 1024 + lane * 16;
-        const int row = min(byte / XS::SEG, rows_here - 1);
-        const int k = min(k0 + (byte % XS::SEG) / 2, K - 8);     // past the end: a valid duplicate
-        tmp[i] = *reinterpret_cast<const u32x4 *>(x + (size_t)(m0 + row) * K + k);
-    }
-}
-
-template <int XR, int BATCH, int N>
-__device__ __forceinline__ void stage_x_store(const u32x4 (&tmp)[N], int first, unsigned char *xbuf, int lane)
-{
-    using XS = XStage<XR, BATCH>;
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int byte = (first + i) * 1024 + lane * 16;
-        *reinterpret_cast<u32x4 *>(xbuf + (byte / XS::SEG) * XS::XROW + byte % XS::SEG) = tmp[i];
-    }
-}
-
-// One batch: BATCH super-steps (BATCH * 4 KiB of codes per wave) are requested before the
-// first is used.  Order: rows of x (the oldest loads, they come from L2), all weight and scale
-// loads, x into LDS as soon as it has arrived, then the math as the weights arrive.  A batch
-// that reaches past count re-reads the last super-step and skips its math.  PREFETCH: after
-// the first super-step the loads the epilogue will need are issued (unconditionally, so that
-// the waits of the remaining super-steps can still be counted).
-template <int MB, int XR, int SPG, int BATCH, bool PREFETCH, class Prefetch>
-__device__ __forceinline__ void stream_batch(f32x4 (&acc)[MB][4], const uint4 *wp, const uint16_t *x, int K,
-                                    int m0, int rows_here, int k_first, const uint2 *sp, int b0,
-                                    int count, unsigned char *xbuf, uint32_t mask, uint32_t bias,
-                                    Prefetch &prefetch, [[maybe_unused]] int trace_slot)
-{
-    using XS = XStage<XR, BATCH>;
-    const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
-    const int k0 = k_first + b0 * SUPER_K;
-    // super-steps past count are requested too (never used): the blob's slack keeps them in bounds
-    const uint4 *wpb = wp + (size_t)b0 * 256;
-    const uint2 *spb = sp + (size_t)b0 * (4 / SPG) * 16;
-    u32x4 xt[XS::NLOAD];
-    stage_x_issue<XR, BATCH>(xt, 0, x, K, m0, rows_here, k0, lane);
-    Stage st[BATCH];
-#pragma unroll
-    for (int i = 0; i < BATCH; ++i) load_stage<SPG>(st[i], wpb, spb, i);
-    stage_x_store<XR, BATCH>(xt, 0, xbuf, lane);
-#pragma unroll
-    for (int i = 0; i < BATCH; ++i) {
-        const unsigned char *xs[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            xs[mb] = xbuf + min(mb * 16 + l16, rows_here - 1) * XS::XROW + 16 * lq + i * (SUPER_K * 2);
-        if (b0 + i < count) compute_stage<MB, SPG>(st[i], xs, acc, mask, bias);
-        if (i == 0) {
-            MLORA_TRACE_POINT(trace_slot, 6);
-            if (PREFETCH) prefetch.issue();
-        }
-    }
-}
-
-template <int MB, int XR, int SPG, int BATCH, class Prefetch>
-__device__ __forceinline__ void stream_k(f32x4 (&acc)[MB][4], const uint4 *wp, const uint16_t *x, int K,
-                                int m0, int rows_here, int k_first, const uint2 *sp, int count,
-                                unsigned char *xbuf, uint32_t mask, uint32_t bias,
-                                Prefetch &prefetch, int trace_slot)
-{
-    const int last = max(count, 1) - 1;
-    int b0 = 0;
-    for (; b0 + BATCH <= last; b0 += BATCH)
-        stream_batch<MB, XR, SPG, BATCH, false>(acc, wp, x, K, m0, rows_here, k_first, sp, b0, count,
-                                            xbuf, mask, bias, prefetch, trace_slot);
-    stream_batch<MB, XR, SPG, BATCH, true>(acc, wp, x, K, m0, rows_here, k_first, sp, b0, count, xbuf,
-                                       mask, bias, prefetch, trace_slot);
 }
 
 // Loads the epilogue needs, issued from inside the K loop (all unconditional; a thread with
@@ -222,6 +194,11 @@ struct EpiPrefetch {
     float t[MAX_KCHUNKS];
     __device__ __forceinline__ void issue()
     {
+        // the addresses pass through an empty asm: without it the compiler hoists these loads to
+        // the top of the kernel and then spills their results across the whole K loop
+#pragma unroll
+        for (int q = 0; q < N; ++q) asm volatile("" : "+v"(brow[q]));
+        if (N > 0) asm volatile("" : "+v"(tp));
 #pragma unroll
         for (int q = 0; q < N; ++q) {
             b[q][0] = *reinterpret_cast<const uint4 *>(brow[q]);
@@ -236,19 +213,19 @@ struct EpiPrefetch {
 
 constexpr int FAST_RANK = 16;                  // the epilogue prefetch covers ranks up to this
 
-// LDS of a base block: the per-wave x staging buffers, reused after the K loop for the
-// per-wave partial tiles, followed by alpha * t of the chunk's rows.
-template <int MB, int XR, int WAVES, int BATCH>
+// LDS of a base block: the per-wave staging buffers; after the K loop the same memory holds the
+// per-wave partial tiles and alpha * t of the chunk's rows.
+template <int MB, int XR, int WAVES, int R>
 struct BaseLds {
-    static constexpr int X_BYTES = WAVES * XStage<XR, BATCH>::BYTES;
+    static constexpr int STAGE_BYTES = WAVES * RoundLds<XR, R>::BYTES;
     static constexpr int RED_BYTES = WAVES * MB * 1024 * 4;
-    static constexpr int FRONT = X_BYTES > RED_BYTES ? X_BYTES : RED_BYTES;
     static constexpr int TS_STRIDE = MLORA_MAX_RANK + 4;
-    static constexpr int BYTES = FRONT + 16 * MB * TS_STRIDE * 4;
+    static constexpr int TS_BYTES = 16 * MB * TS_STRIDE * 4;
+    static constexpr int BYTES = STAGE_BYTES > RED_BYTES + TS_BYTES ? STAGE_BYTES : RED_BYTES + TS_BYTES;
     unsigned char *base;
-    __device__ unsigned char *xbuf(int wave) const { return base + wave * XStage<XR, BATCH>::BYTES; }
+    __device__ unsigned char *stage(int wave) const { return base + wave * RoundLds<XR, R>::BYTES; }
     __device__ float *red(int wave) const { return reinterpret_cast<float *>(base) + wave * MB * 1024; }
-    __device__ float *t_row(int ml) const { return reinterpret_cast<float *>(base + FRONT) + ml * TS_STRIDE; }
+    __device__ float *t_row(int ml) const { return reinterpret_cast<float *>(base + RED_BYTES) + ml * TS_STRIDE; }
 };
 
 __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
@@ -268,9 +245,9 @@ __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
 // WAVES waves split the unit's super-steps; thread (wave w, lane l) then finishes the EPT tile
 // elements i = w*EPT .. +EPT-1, element i = (mb, j, e) being row 16*mb + 4*(l/16) + e, column
 // 16*j + l%16 (the MFMA result layout).
-template <int MB, int XR, int WAVES, int BATCH>
+template <int MB, int XR, int WAVES, int R>
 __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int tile, int ku, int m0,
-                                 const BaseLds<MB, XR, WAVES, BATCH> &lds)
+                                 const BaseLds<MB, XR, WAVES, R> &lds)
 {
     constexpr int ROWS = 16 * MB;
     constexpr int NT = 64 * WAVES;
@@ -292,29 +269,24 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 
     const int ksteps = K / KSTEP;
     const int ngroups = ksteps / P.spg;
-    const uint4 *wp = P.codes + ((size_t)tile * ksteps + (size_t)my_beg * 4) * 64 + lane;
-    const uint2 *sp = P.scales + ((size_t)tile * ngroups + (size_t)my_beg * (4 / P.spg)) * 16 + l16;
+    const uint4 *codes_tile = P.codes + (size_t)tile * ksteps * 64;
+    const uint2 *scales_tile = P.scales + (size_t)tile * ngroups * 16;
 
     // what this thread will finish, and the adapter of each of its rows
     const bool lora = (ku == 0) && (a.row_adapter != nullptr) && (P.n_adapters > 0);
     const int rows_here = min(ROWS, M - m0);
     constexpr bool PREFETCH = EPT <= 4;                    // more outputs per thread: too many registers
     const bool fast = PREFETCH && lora && P.rank <= FAST_RANK && rows_here * P.r16 <= NT;
+    // element qq of this thread: tile row and column (cheap to recompute, so not kept live)
+    auto elem_ml = [&](int qq) { const int i = wave * EPT + qq; return (i >> 4) * 16 + 4 * lq + (i & 3); };
+    auto elem_col = [&](int qq) { const int i = wave * EPT + qq; return 16 * ((i >> 2) & 3) + l16; };
     const int *ra_safe = lora ? a.row_adapter : reinterpret_cast<const int *>(P.codes);
-    int out_ml[EPT], out_col[EPT], out_ad[EPT];
-    const int ra_last = lora ? M - 1 : 0;                  // unconditional loads, decoded below
-#pragma unroll
-    for (int qq = 0; qq < EPT; ++qq) {
-        const int i = wave * EPT + qq;
-        out_ml[qq] = (i >> 4) * 16 + 4 * lq + (i & 3);
-        out_col[qq] = 16 * ((i >> 2) & 3) + l16;
-        out_ad[qq] = ra_safe[min(m0 + out_ml[qq], ra_last)];
-    }
-#pragma unroll
-    for (int qq = 0; qq < EPT; ++qq) {
-        const int v = out_ad[qq];
-        out_ad[qq] = (lora && m0 + out_ml[qq] < M && v >= 0 && v < P.n_adapters) ? v : -1;
-    }
+    const int ra_last = lora ? M - 1 : 0;
+    int ad_raw[EPT];
+    auto elem_ad = [&](int qq) {
+        const int v = ad_raw[qq];
+        return (lora && m0 + elem_ml(qq) < M && v >= 0 && v < P.n_adapters) ? v : -1;
+    };
 
     f32x4 acc[MB][4];
 #pragma unroll
@@ -323,37 +295,70 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     MLORA_TRACE_POINT(trace_slot, 1);
 
-    // epilogue operands fetched while the last super-steps are still being computed: the rows
-    // of B of this thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
+    // epilogue operands fetched while the last round is being computed: the rows of B of this
+    // thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
     EpiPrefetch<PREFETCH ? EPT : 0> pf;
-    pf.t_ml = tid / max(P.r16, 1);
-    pf.t_jj = tid % max(P.r16, 1);
-    pf.t_mine = fast && tid < rows_here * P.r16;
-    {
+    auto prefetch_setup = [&]() {
+        pf.t_ml = tid / max(P.r16, 1);
+        pf.t_jj = tid % max(P.r16, 1);
+        pf.t_mine = fast && tid < rows_here * P.r16;
         const uint16_t *safe = reinterpret_cast<const uint16_t *>(P.codes);
 #pragma unroll
         for (int qq = 0; qq < (PREFETCH ? EPT : 0); ++qq) {
-            const int n = tile * TILE_N + out_col[qq];
-            const bool ok = fast && out_ad[qq] >= 0 && n < N;
-            pf.brow[qq] = ok ? P.lora_b + ((size_t)out_ad[qq] * N + n) * P.rank : safe;
+            const int n = tile * TILE_N + elem_col(qq);
+            const int ad = elem_ad(qq);
+            const bool ok = fast && ad >= 0 && n < N;
+            pf.brow[qq] = ok ? P.lora_b + ((size_t)ad * N + n) * P.rank : safe;
             pf.bstep[qq] = ok ? P.rank - 8 : 0;
         }
         pf.tp = pf.t_mine ? P.t_part + (size_t)(m0 + pf.t_ml) * P.r16 + pf.t_jj
                           : reinterpret_cast<const float *>(P.codes);
         pf.tstride = pf.t_mine ? (size_t)M * P.r16 : 0;
         pf.kch = P.kch;
-    }
+    };
 
     // the two constants of expand_codes arrive as kernel arguments so that they live in
     // registers and each field pair costs one and-or instead of an and plus an or with literals
     const uint32_t mask = a.code_mask;
     uint32_t bias = a.code_bias;
     asm volatile("" : "+v"(bias));      // pin to a vector register (one scalar operand per op)
-    unsigned char *xbuf = lds.xbuf(wave);
-    const int k_first = my_beg * SUPER_K;
-    if (P.spg == 1)      stream_k<MB, XR, 1, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
-    else if (P.spg == 2) stream_k<MB, XR, 2, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
-    else                 stream_k<MB, XR, 4, BATCH>(acc, wp, P.x, K, m0, rows_here, k_first, sp, my_cnt, xbuf, mask, bias, pf, trace_slot);
+
+    // K loop: pairs of rounds.  An idle wave (my_cnt == 0) still requests one pair at a valid
+    // place and computes nothing.
+    unsigned char *buf = lds.stage(wave);
+    const int ks_first = my_beg * 4, ks_total = my_cnt * 4;
+    const int rows_x = min(rows_here, XR);
+    for (int r0 = 0; r0 < max(ks_total, 1); r0 += 2 * R) {
+        RoundRegs<XR, R> ra, rb;
+        round_issue_w<XR, R>(ra, codes_tile, ks_first + r0, lane);
+        round_issue_xs<XR, R>(ra, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0, lane);
+        round_issue_w<XR, R>(rb, codes_tile, ks_first + r0 + R, lane);
+        round_issue_xs<XR, R>(rb, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0 + R, lane);
+        // adapters of this thread's rows: requested here (unconditionally), decoded when needed
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq) ad_raw[qq] = ra_safe[min(m0 + elem_ml(qq), ra_last)];
+        // keep the second round's requests ahead of the first wait: the scheduler would
+        // otherwise sink them below it to save registers, which halves the bytes in flight
+        __builtin_amdgcn_sched_barrier(0);
+        const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
+        round_to_lds<XR, R>(ra, buf, lane);
+        // epilogue operands: requested as soon as the first round's registers are free, in
+        // flight while both rounds are computed.  (The empty asm keeps the decoding of the
+        // adapter indices, and with it the wait for their loads, from being hoisted.)
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq) asm volatile("" : "+v"(ad_raw[qq]));
+        prefetch_setup();
+        pf.issue();
+        __builtin_amdgcn_sched_barrier(0);
+        if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, na, rows_x, mask, bias, lane);
+        else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, na, rows_x, mask, bias, lane);
+        else                 round_compute<MB, XR, R, 4>(acc, buf, na, rows_x, mask, bias, lane);
+        MLORA_TRACE_POINT(trace_slot, 6);
+        round_to_lds<XR, R>(rb, buf, lane);
+        if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, nb, rows_x, mask, bias, lane);
+        else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, nb, rows_x, mask, bias, lane);
+        else                 round_compute<MB, XR, R, 4>(acc, buf, nb, rows_x, mask, bias, lane);
+    }
 
     MLORA_TRACE_POINT(trace_slot, 2);
     // partial tiles -> LDS (over the staging buffers, once every wave is done reading them)
@@ -402,7 +407,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) v += lds.red(w)[off];
         if (qq == 0) MLORA_TRACE_POINT(trace_slot, 7);
-        const int ml = out_ml[qq], col = out_col[qq];
+        const int ml = elem_ml(qq), col = elem_col(qq);
         const int m = m0 + ml;
         const int n = tile * TILE_N + col;
         if (ku > 0) {
@@ -412,7 +417,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         if (m < M && n < N) {
             for (int u = 1; u < P.ksplit; ++u)
                 v += P.partial[(((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col];
-            const int ad = out_ad[qq];
+            const int ad = elem_ad(qq);
             if (ad >= 0) {
                 float l = 0.f;
                 if (fast) {
@@ -525,14 +530,14 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
 // kernels
 // ------------------------------------------------------------------------------------------
 // MB blocks of 16 rows per chunk, XR rows staged in LDS (the smallest multiple of 8 that holds
-// the rows of a chunk decides which instance runs): 4 waves per block; up to 16 rows a wave
-// keeps 4 super-steps (16 KiB of codes) in flight, above that 2.
+// the rows of a chunk decides which instance runs): 4 waves per block, rounds of R k-steps
+// (two rounds = 2*R KiB of codes in flight per wave).
 template <int MB> struct Shape;
-template <> struct Shape<1> { static constexpr int WAVES = 4, BATCH = 4, OCC = 2; };
-template <> struct Shape<2> { static constexpr int WAVES = 4, BATCH = 2, OCC = 2; };
+template <> struct Shape<1> { static constexpr int WAVES = 4, R = 8, OCC = 2; };
+template <> struct Shape<2> { static constexpr int WAVES = 4, R = 4, OCC = 2; };
 
 template <int MB, int XR>
-using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>;
+using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>;
 template <int MB, int XR>
 constexpr int pre_lds_bytes()
 {
@@ -558,7 +563,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_p
         const ProjArgs &P = a.p[pi];
         const int local = b - a.pre_begin[pi];
         const int tiles = tiles_n(P.N);
-        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>(a, P, local % tiles, 1 + local / tiles,
+        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, local % tiles, 1 + local / tiles,
                                                               (int)blockIdx.y * 16 * MB, lds);
     } else {
         if (blockIdx.y != 0) return;
@@ -575,7 +580,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_m
     const BaseLdsOf<MB, XR> lds{smem};
     const int b = (int)blockIdx.x;
     const int pi = find_proj(a.main_begin, a.n_proj, b);
-    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::BATCH>(a, a.p[pi], b - a.main_begin[pi], 0,
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, a.p[pi], b - a.main_begin[pi], 0,
                                                           (int)blockIdx.y * 16 * MB, lds);
 }
 
