@@ -168,6 +168,8 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
         a.n_proj = count;
         a.M = M;
         a.y_fp32 = (y_dtype == MLORA_Y_FP32);
+        for (int i = 0; i < MAX_PROJ_PER_LAUNCH; ++i)
+            a.main_begin[i] = a.pre_begin[i] = a.shrink_begin[i] = 0x7FFFFFFF;
         a.m_pad = m_pad_of(M);
         a.code_mask = 0x00780078u;
         a.code_bias = 0x41804180u;

@@ -340,6 +340,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         // keep the second round's requests ahead of the first wait: the scheduler would
         // otherwise sink them below it to save registers, which halves the bytes in flight
         __builtin_amdgcn_sched_barrier(0);
+        MLORA_TRACE_POINT(trace_slot, 7);
         const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
         round_to_lds<XR, R>(ra, buf, lane);
         // epilogue operands: requested as soon as the first round's registers are free, in
@@ -361,6 +362,21 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     }
 
     MLORA_TRACE_POINT(trace_slot, 2);
+    // split-K partials of this thread's outputs: all requested at once (a thread with nothing to
+    // add re-reads a valid address), consumed after the reduction below
+    constexpr int PU = 3;
+    const int tiles = tiles_n(N);
+    float pv[EPT][PU];
+#pragma unroll
+    for (int qq = 0; qq < EPT; ++qq)
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int m = m0 + elem_ml(qq);
+            const bool ok = ku == 0 && u + 1 < P.ksplit && m < M;
+            const float *src = ok ? P.partial + (((size_t)u * tiles + tile) * a.m_pad + m) * TILE_N + elem_col(qq)
+                                  : reinterpret_cast<const float *>(P.codes);
+            pv[qq][u] = *src;
+        }
     // partial tiles -> LDS (over the staging buffers, once every wave is done reading them)
     __syncthreads();
     {
@@ -398,7 +414,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     __syncthreads();
     MLORA_TRACE_POINT(trace_slot, 4);
 
-    const int tiles = tiles_n(N);
 #pragma unroll
     for (int qq = 0; qq < EPT; ++qq) {
         const int i = wave * EPT + qq;
@@ -406,7 +421,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         float v = lds.red(0)[off];
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) v += lds.red(w)[off];
-        if (qq == 0) MLORA_TRACE_POINT(trace_slot, 7);
         const int ml = elem_ml(qq), col = elem_col(qq);
         const int m = m0 + ml;
         const int n = tile * TILE_N + col;
@@ -415,7 +429,10 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             continue;
         }
         if (m < M && n < N) {
-            for (int u = 1; u < P.ksplit; ++u)
+#pragma unroll
+            for (int u = 0; u < PU; ++u)
+                if (u + 1 < P.ksplit) v += pv[qq][u];
+            for (int u = PU + 1; u < P.ksplit; ++u)
                 v += P.partial[(((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col];
             const int ad = elem_ad(qq);
             if (ad >= 0) {
@@ -544,11 +561,32 @@ constexpr int pre_lds_bytes()
     return BaseLdsOf<MB, XR>::BYTES > (int)sizeof(ShrinkLds) ? BaseLdsOf<MB, XR>::BYTES : (int)sizeof(ShrinkLds);
 }
 
-__device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH], int n_proj, int b)
+// Fetch every field of a projection's argument block at once.  Kernel arguments sit behind a
+// scalar cache that is cold at every launch (about 0.4 us per dependent access); left alone,
+// the compiler loads each field where it is first used, one round trip after another.  Pinning
+// all fields to registers at one point makes it issue the loads together.
+__device__ __forceinline__ ProjArgs fetch_proj(const LayerArgs &a, int pi)
+{
+    ProjArgs P = a.p[pi];
+    asm volatile("" :: "s"(P.codes), "s"(P.scales), "s"(P.x), "s"(P.y), "s"(P.lora_a), "s"(P.lora_b),
+                 "s"(P.t_part), "s"(P.partial));
+    asm volatile("" :: "s"(P.K), "s"(P.N), "s"(P.spg), "s"(P.n_adapters), "s"(P.rank), "s"(P.r16),
+                 "s"(P.kch), "s"(P.alpha), "s"(P.ksplit));
+    return P;
+}
+
+// Entries past the last projection hold INT_MAX, so all 16 comparisons can be made without a
+// loop: the table arrives with one scalar load instead of one dependent load per projection.
+// first = begin[pi], picked from the same registers (begins are non-decreasing).
+__device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH], int b, int &first)
 {
     int pi = 0;
-    for (int i = 1; i < n_proj; ++i)
-        if (b >= begin[i]) pi = i;
+    first = begin[0];
+#pragma unroll
+    for (int i = 1; i < MAX_PROJ_PER_LAUNCH; ++i) {
+        pi += (b >= begin[i]) ? 1 : 0;
+        first = (b >= begin[i]) ? begin[i] : first;
+    }
     return pi;
 }
 
@@ -559,17 +597,19 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_p
     const int b = (int)blockIdx.x;
     if (b < a.pre_base_blocks) {
         const BaseLdsOf<MB, XR> lds{smem};
-        const int pi = find_proj(a.pre_begin, a.n_proj, b);
-        const ProjArgs &P = a.p[pi];
-        const int local = b - a.pre_begin[pi];
+        int first;
+        const int pi = find_proj(a.pre_begin, b, first);
+        const ProjArgs P = fetch_proj(a, pi);
+        const int local = b - first;
         const int tiles = tiles_n(P.N);
         base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, local % tiles, 1 + local / tiles,
                                                               (int)blockIdx.y * 16 * MB, lds);
     } else {
         if (blockIdx.y != 0) return;
         const int sb = b - a.pre_base_blocks;
-        const int pi = find_proj(a.shrink_begin, a.n_proj, sb);
-        shrink_block(a, a.p[pi], sb - a.shrink_begin[pi], *reinterpret_cast<ShrinkLds *>(smem));
+        int first;
+        const int pi = find_proj(a.shrink_begin, sb, first);
+        shrink_block(a, fetch_proj(a, pi), sb - first, *reinterpret_cast<ShrinkLds *>(smem));
     }
 }
 
@@ -579,8 +619,10 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_m
     __shared__ __align__(16) unsigned char smem[BaseLdsOf<MB, XR>::BYTES];
     const BaseLdsOf<MB, XR> lds{smem};
     const int b = (int)blockIdx.x;
-    const int pi = find_proj(a.main_begin, a.n_proj, b);
-    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, a.p[pi], b - a.main_begin[pi], 0,
+    int first;
+    const int pi = find_proj(a.main_begin, b, first);
+    const ProjArgs P = fetch_proj(a, pi);
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, b - first, 0,
                                                           (int)blockIdx.y * 16 * MB, lds);
 }
 
