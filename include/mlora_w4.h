@@ -102,8 +102,19 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                               int32_t *perm, int32_t *seg_adapter, int32_t *seg_start,
                               int32_t *n_seg, void *stream);
 
-/* Device scratch a call over these projections and M rows needs (256-byte aligned pointer). */
+/* Device scratch a call over these projections and M rows needs (256-byte aligned pointer).
+ * It holds what blocks of one launch hand to each other: the inner LoRA factor t[m] = A[a(m)].x[m]
+ * of Eq. 1-4, partial base products of projections with more than 2048 inputs, and the
+ * completion counters that order them.  The counters must be ZERO when a call starts and are
+ * zero again when it ends: call mlora_w4_workspace_init once after allocating a workspace (or
+ * hand in zero-filled memory); calls that overlap in time need a workspace each.  The first
+ * uint32 of the workspace is a status word: it stays 0 unless a block gave up waiting for
+ * another (which only a foreign write to the counters can cause); the results of that call are
+ * then invalid and the workspace has to be initialised again. */
 size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M);
+
+/* Zero-fill a workspace (a small kernel on `stream`; no memset node, so it can be captured). */
+mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* One projection.
  *   x            bf16 [M][K]
@@ -115,7 +126,7 @@ mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_
                              size_t workspace_bytes, void *stream);
 
 /* Several independent projections over the same M rows and the same row->adapter index in as
- * few launches as possible: the seven projections of a decoder block (Section 3.1), or more.
+ * one launch per 16 projections: the seven projections of a decoder block (Section 3.1), or more.
  *   xs[i], ys[i]  device pointers of projection i (host arrays of n_proj pointers); inputs may
  *                 be shared (q, k, v read the same rows), outputs may not
  * Ordering against whatever produces the inputs is the caller's business. */
@@ -123,22 +134,6 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                                  const void *const *xs, void *const *ys,
                                  const int32_t *row_adapter, int32_t M, int32_t y_dtype,
                                  void *workspace, size_t workspace_bytes, void *stream);
-
-/* The same call split at its one internal dependency, for timing each launch on its own:
- *   MLORA_PHASE_PRE   everything the finishing launch depends on: group rows by adapter and
- *                     compute t[m] = A[a(m)].x[m] (the inner factor of the LoRA term of Eq. 1-4),
- *                     plus, for projections with more than 2048 inputs, the partial base
- *                     products of all but the first 2048-input slice; all left in the workspace
- *   MLORA_PHASE_MAIN  base product (first slice plus the stored partials) + alpha*B[a(m)].t[m],
- *                     stores y
- * phases = MLORA_PHASE_PRE | MLORA_PHASE_MAIN is mlora_w4_layer_step.  MLORA_PHASE_MAIN alone
- * needs the workspace left by a MLORA_PHASE_PRE call with the same arguments. */
-enum { MLORA_PHASE_PRE = 1, MLORA_PHASE_MAIN = 2 };
-mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_proj,
-                                        const void *const *xs, void *const *ys,
-                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
-                                        void *workspace, size_t workspace_bytes, void *stream,
-                                        int32_t phases);
 
 const char *mlora_strerror(mlora_status status);
 

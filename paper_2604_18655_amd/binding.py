@@ -15,9 +15,8 @@ Y_BF16, Y_FP32 = 0, 1
 exported_symbols = (
     "mlora_strerror", "mlora_w4_blob_bytes", "mlora_w4_prepack", "mlora_w4_unpack",
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
-    "mlora_w4_layer_step_phases",
+    "mlora_w4_workspace_init",
 )
-PHASE_PRE, PHASE_MAIN = 1, 2
 
 
 class MloraError(RuntimeError):
@@ -63,9 +62,8 @@ def load_library():
         lib.mlora_w4_layer_step.restype = C.c_int
         lib.mlora_w4_layer_step.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32, i32,
                                             vp, sz, vp]
-        lib.mlora_w4_layer_step_phases.restype = C.c_int
-        lib.mlora_w4_layer_step_phases.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32,
-                                                   i32, vp, sz, vp, i32]
+        lib.mlora_w4_workspace_init.restype = C.c_int
+        lib.mlora_w4_workspace_init.argtypes = [vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -136,6 +134,12 @@ def group_rows(row_adapter, M: int, n_adapters: int, perm, seg_adapter, seg_star
                                            _stream()), "mlora_group_rows")
 
 
+def workspace_init(workspace) -> None:
+    n = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().mlora_w4_workspace_init(_ptr(workspace), n, _stream()),
+           "mlora_w4_workspace_init")
+
+
 def workspace_bytes(projs: Sequence[Proj], M: int) -> int:
     arr = _proj_array(projs)
     return int(load_library().mlora_w4_workspace_bytes(arr, len(projs), M))
@@ -166,20 +170,12 @@ class LayerPlan:
         self.ws = _ptr(workspace)
         self.ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         self.fn = load_library().mlora_w4_layer_step
-        self.fn_phases = load_library().mlora_w4_layer_step_phases
 
     def run(self, stream: Optional[int] = None) -> None:
         st = self.fn(self.arr, self.n, self.xs, self.ys, self.rows, self.M, self.y_dtype,
                      self.ws, self.ws_bytes, _stream() if stream is None else stream)
         if st != 0:
             raise MloraError(st, "mlora_w4_layer_step")
-
-    def run_phases(self, phases: int, stream: Optional[int] = None) -> None:
-        st = self.fn_phases(self.arr, self.n, self.xs, self.ys, self.rows, self.M, self.y_dtype,
-                            self.ws, self.ws_bytes, _stream() if stream is None else stream,
-                            phases)
-        if st != 0:
-            raise MloraError(st, "mlora_w4_layer_step_phases")
 
 
 def layer_step(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,

@@ -121,22 +121,54 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                              (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }
 
+// Workspace layout: [status word, 256 B][counters of launch 0][counters of launch 1]...[data].
+// Counters exist only if something is shared between blocks (LoRA or split-K).
+static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M, bool lora)
+{
+    size_t n = 0;
+    bool any = false;
+    for (int i = 0; i < count; ++i) {
+        if (ksplit_of(projs[i]) > 1) {
+            n += (size_t)tiles_n(projs[i].N) * (size_t)(m_pad_of(M) / rows_per_chunk(M));
+            any = true;
+        }
+        any = any || (lora && projs[i].n_adapters > 0);
+    }
+    return any ? round_up((CTRL_PART + n) * sizeof(unsigned), 256) : 0;
+}
+
+static size_t ctrl_bytes_total(const mlora_w4_proj *projs, int n_proj, int M, bool lora)
+{
+    size_t total = 0;
+    for (int first = 0; first < n_proj; first += MAX_PROJ_PER_LAUNCH) {
+        const int count = (n_proj - first < MAX_PROJ_PER_LAUNCH) ? n_proj - first : MAX_PROJ_PER_LAUNCH;
+        total += ctrl_bytes_of_launch(projs + first, count, M, lora);
+    }
+    return total ? total + WS_HEADER_BYTES : 0;
+}
+
 size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M)
 {
     if (!projs || n_proj <= 0 || M <= 0) return 0;
-    size_t total = 0;
+    size_t total = ctrl_bytes_total(projs, n_proj, M, true);
     for (int i = 0; i < n_proj; ++i) total += t_part_bytes(projs[i], M) + partial_bytes(projs[i], M);
     return total;
 }
 
-mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_proj,
-                                        const void *const *xs, void *const *ys,
-                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
-                                        void *workspace, size_t workspace_bytes, void *stream,
-                                        int32_t phases)
+mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return workspace_bytes == 0 ? MLORA_OK : MLORA_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
+    return launch_zero(workspace, workspace_bytes / 16 * 16, (hipStream_t)stream) == hipSuccess
+               ? MLORA_OK : MLORA_EHIP;
+}
+
+mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                 const void *const *xs, void *const *ys,
+                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!projs || !xs || !ys || n_proj <= 0) return MLORA_EINVAL;
-    if (phases < 1 || phases > (MLORA_PHASE_PRE | MLORA_PHASE_MAIN)) return MLORA_EINVAL;
     if (y_dtype != MLORA_Y_BF16 && y_dtype != MLORA_Y_FP32) return MLORA_EINVAL;
     if (M < 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
     bool any_lora = false;
@@ -159,7 +191,9 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
     }
 
     hipStream_t s = (hipStream_t)stream;
-    char *ws = reinterpret_cast<char *>(workspace);
+    char *ctrl = reinterpret_cast<char *>(workspace) + WS_HEADER_BYTES;
+    char *ws = reinterpret_cast<char *>(workspace) + ctrl_bytes_total(projs, n_proj, M, true);
+    const int chunks = m_pad_of(M) / rows_per_chunk(M);
     for (int first = 0; first < n_proj; first += MAX_PROJ_PER_LAUNCH) {
         const int count = (n_proj - first < MAX_PROJ_PER_LAUNCH) ? n_proj - first : MAX_PROJ_PER_LAUNCH;
         LayerArgs a;
@@ -173,7 +207,12 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
         a.m_pad = m_pad_of(M);
         a.code_mask = 0x00780078u;
         a.code_bias = 0x41804180u;
-        int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0;
+        if (need > 0) {
+            a.status = reinterpret_cast<unsigned *>(workspace);
+            a.ctrl = reinterpret_cast<unsigned *>(ctrl);
+            ctrl += ctrl_bytes_of_launch(projs + first, count, M, true);
+        }
+        int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0, part_ctr = CTRL_PART;
         for (int i = 0; i < count; ++i) {
             const mlora_w4_proj &p = projs[first + i];
             ProjArgs &d = a.p[i];
@@ -187,12 +226,15 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
             d.spg = p.group / KSTEP;
             d.alpha = p.alpha;
             d.ksplit = ksplit_of(p);
+            d.n_finish_blocks = tiles_n(p.N) * chunks;
             a.main_begin[i] = main_blocks;
             main_blocks += tiles_n(p.N);
             a.pre_begin[i] = pre_blocks;
             pre_blocks += tiles_n(p.N) * (d.ksplit - 1);
             d.partial = reinterpret_cast<float *>(ws);
             ws += partial_bytes(p, M);
+            d.part_ctr = part_ctr;
+            if (d.ksplit > 1) part_ctr += tiles_n(p.N) * chunks;
             a.shrink_begin[i] = shrink_blocks;
             if (any_lora && p.n_adapters > 0) {
                 d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);
@@ -203,7 +245,8 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
                 d.kch = kch_of(p);
                 d.t_part = reinterpret_cast<float *>(ws);
                 ws += t_part_bytes(p, M);
-                shrink_blocks += max_row_tiles(M, p.n_adapters) * (d.r16 / 16) * d.kch;
+                d.n_shrink_blocks = max_row_tiles(M, p.n_adapters) * (d.r16 / 16) * d.kch;
+                shrink_blocks += d.n_shrink_blocks;
             } else {
                 d.n_adapters = 0;
                 d.rank = 0;
@@ -211,22 +254,11 @@ mlora_status mlora_w4_layer_step_phases(const mlora_w4_proj *projs, int32_t n_pr
                 d.kch = 1;
             }
         }
+        a.shrink_blocks = shrink_blocks;
         a.pre_base_blocks = pre_blocks;
-        if ((phases & MLORA_PHASE_PRE) && pre_blocks + shrink_blocks > 0 &&
-            launch_pre(a, pre_blocks + shrink_blocks, s) != hipSuccess) return MLORA_EHIP;
-        if ((phases & MLORA_PHASE_MAIN) && launch_main(a, main_blocks, s) != hipSuccess) return MLORA_EHIP;
+        if (launch_layer(a, shrink_blocks + pre_blocks + main_blocks, s) != hipSuccess) return MLORA_EHIP;
     }
     return MLORA_OK;
-}
-
-mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
-                                 const void *const *xs, void *const *ys,
-                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
-                                 void *workspace, size_t workspace_bytes, void *stream)
-{
-    return mlora_w4_layer_step_phases(projs, n_proj, xs, ys, row_adapter, M, y_dtype, workspace,
-                                      workspace_bytes, stream,
-                                      MLORA_PHASE_PRE | MLORA_PHASE_MAIN);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,

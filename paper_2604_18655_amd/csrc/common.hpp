@@ -73,21 +73,34 @@ struct ProjArgs {
     int kch;                   // number of K chunks of the shrink step
     float alpha;
     int ksplit;                // K units per tile; unit 0 finishes the tile, the others run ahead
+    int n_shrink_blocks;       // shrink blocks of this projection (each bumps its counter once)
+    int n_finish_blocks;       // finishing blocks of this projection (tiles x row chunks)
+    int part_ctr;              // index of this projection's first split-K counter in ctrl
 };
 
+// Counters in the workspace that order the blocks of one launch (all zero between calls):
+//   ctrl[p]            shrink blocks of projection p that have finished
+//   ctrl[16 + p]       finishing blocks of projection p that have seen them all (the last resets both)
+//   ctrl[part_ctr + tile * chunks + chunk]   split-K units of that tile that have finished
+constexpr int CTRL_SHRINK_DONE = 0, CTRL_SHRINK_USED = MAX_PROJ_PER_LAUNCH, CTRL_PART = 2 * MAX_PROJ_PER_LAUNCH;
+constexpr size_t WS_HEADER_BYTES = 256;        // status word at the front of every workspace
+
 struct LayerArgs {
-    // first block of each projection: in the main launch, among the split-K blocks of the pre
-    // launch, and among its shrink blocks (which follow all split-K blocks)
-    int main_begin[MAX_PROJ_PER_LAUNCH];
-    int pre_begin[MAX_PROJ_PER_LAUNCH];
+    // One launch holds, in this order, the shrink blocks, the split-K blocks (units 1..) and the
+    // finishing blocks (unit 0) of all projections; first block of each projection in each group:
     int shrink_begin[MAX_PROJ_PER_LAUNCH];
+    int pre_begin[MAX_PROJ_PER_LAUNCH];
+    int main_begin[MAX_PROJ_PER_LAUNCH];
     ProjArgs p[MAX_PROJ_PER_LAUNCH];
     const int *row_adapter;    // may be null
     int n_proj;
     int M;
     int y_fp32;
     int m_pad;                 // M rounded up to whole row chunks of the base kernel
-    int pre_base_blocks;       // split-K blocks in the pre launch; shrink blocks follow them
+    int shrink_blocks;         // number of shrink blocks (first in the grid)
+    int pre_base_blocks;       // number of split-K blocks (after the shrink blocks)
+    unsigned *ctrl;            // completion counters of this launch
+    unsigned *status;          // workspace status word: set non-zero if a wait ran out
     uint32_t code_mask;        // 0x00780078: the two code fields of a bf16 pair
     uint32_t code_bias;        // 0x41804180: sign, exponent and leading mantissa bit of 16.0
 };
@@ -119,12 +132,12 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
 // Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
 // library build); each wave appends (constant-rate clock, shader clock) pairs to a buffer.
 #ifdef MLORA_TRACE
-extern __device__ unsigned long long *g_trace;           // [n_waves][16]
+extern __device__ unsigned long long *g_trace;           // [n_waves][32]
 #define MLORA_TRACE_POINT(slot, id)                                                        \
     do {                                                                                   \
         if (g_trace && (threadIdx.x & 63) == 0) {                                          \
-            g_trace[(size_t)(slot) * 16 + 2 * (id)] = wall_clock64();                      \
-            g_trace[(size_t)(slot) * 16 + 2 * (id) + 1] = clock64();                       \
+            g_trace[(size_t)(slot) * 32 + 2 * (id)] = wall_clock64();                      \
+            g_trace[(size_t)(slot) * 32 + 2 * (id) + 1] = clock64();                       \
         }                                                                                  \
     } while (0)
 #else
@@ -138,10 +151,8 @@ hipError_t launch_unpack(int K, int N, int group, const void *blob, int8_t *code
                          hipStream_t s);
 hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int *perm,
                              int *seg_adapter, int *seg_start, int *n_seg, hipStream_t s);
-// pre launch: split-K units 1.. of long-K projections plus the group + shrink blocks;
-// main launch: unit 0 of every tile, which also adds the partials and the LoRA term
-hipError_t launch_pre(const LayerArgs &a, int n_blocks, hipStream_t s);
-hipError_t launch_main(const LayerArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
 __host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : 32; }

@@ -1,4 +1,4 @@
-// The two launches of a layer step.
+// The layer step: one launch.
 //
 // Base product.  A block of four waves owns one K unit (at most 2048 inputs) of one tile of 64
 // output columns for one chunk of 16*MB rows.  Each wave issues ALL loads of its share up
@@ -8,11 +8,18 @@
 // Scales multiply the fp32 result of each scale group, so codes enter the matrix unit exactly.
 // The four partial tiles are added in LDS in a fixed order.
 //
-// Projections with more than 2048 inputs are cut into several K units per tile: units 1.. run
-// in the pre launch and leave fp32 partial tiles in the workspace; unit 0 runs in the main
-// launch, adds them in order, adds the LoRA term alpha * B[a(m)][n] . t[m] and stores y.
+// Projections with more than 2048 inputs are cut into several K units per tile: units 1..
+// leave fp32 partial tiles in the workspace; unit 0 (the finishing block) adds them in order,
+// adds the LoRA term alpha * B[a(m)][n] . t[m] and stores y.
 //
-// LoRA shrink (pre launch, next to the split-K units).  A block owns one (16-row tile of an
+// Order inside the launch.  The grid holds the shrink blocks first, then the split-K blocks,
+// then the finishing blocks.  A finishing block streams its weights without waiting for
+// anything; only before its epilogue does it wait (bounded spin on counters in the workspace)
+// until the shrink blocks of its projection and the split-K blocks of its tile have signalled
+// completion.  Blocks are dispatched in index order, producers never wait, so every wait
+// ends; if one nevertheless runs out, the block sets the workspace status word and goes on.
+//
+// LoRA shrink.  A block owns one (16-row tile of an
 // adapter segment, block of 16 ranks, K chunk): after grouping the rows in LDS its four waves
 // split the chunk, each accumulating a 16x16 tile with MFMA (A operand: rows of x, B operand:
 // 16 rows of A[adapter]); the sum goes to t_part[chunk][row][rank].
@@ -27,6 +34,43 @@ extern "C" hipError_t mlora_trace_set(unsigned long long *p)
     return hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof p);
 }
 #endif
+
+// ------------------------------------------------------------------------------------------
+// completion counters
+// ------------------------------------------------------------------------------------------
+constexpr int SPIN_LIMIT = 200000;            // x ~0.5 us: far beyond any launch, still finite
+
+// Data one block hands to another inside a launch (split-K partial tiles, the shrink step's t)
+// is written and read with agent-scope accesses: they go through to memory and are re-fetched
+// from it, so no cache of a compute unit or of a die ever holds a stale copy of it, and no
+// cache-wide write-back or invalidate (which every fence at that scope costs) is needed.
+__device__ __forceinline__ void store_shared(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_shared(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// all threads of the block, after their store_shared calls: wait until the own stores have been
+// acknowledged, meet, then count the block as done
+__device__ __forceinline__ void signal_done(unsigned *counter)
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): every store of this wave has completed
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(counter, 1u);
+}
+
+// one thread: wait until *counter has reached expected; false if the wait ran out
+__device__ __forceinline__ bool wait_count(unsigned *counter, unsigned expected)
+{
+    for (int i = 0; i < SPIN_LIMIT; ++i) {
+        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) return true;
+        __builtin_amdgcn_s_sleep(8);
+    }
+    return false;
+}
 
 // ------------------------------------------------------------------------------------------
 // base product
@@ -191,22 +235,16 @@ struct EpiPrefetch {
     int kch, t_ml, t_jj;
     bool t_mine;
     uint4 b[N > 0 ? N : 1][2];
-    float t[MAX_KCHUNKS];
     __device__ __forceinline__ void issue()
     {
         // the addresses pass through an empty asm: without it the compiler hoists these loads to
         // the top of the kernel and then spills their results across the whole K loop
 #pragma unroll
         for (int q = 0; q < N; ++q) asm volatile("" : "+v"(brow[q]));
-        if (N > 0) asm volatile("" : "+v"(tp));
 #pragma unroll
         for (int q = 0; q < N; ++q) {
             b[q][0] = *reinterpret_cast<const uint4 *>(brow[q]);
             b[q][1] = *reinterpret_cast<const uint4 *>(brow[q] + min(8, bstep[q]));
-        }
-        if (N > 0) {
-#pragma unroll
-            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) t[kc] = tp[(size_t)min(kc, kch - 1) * tstride];
         }
     }
 };
@@ -246,8 +284,8 @@ __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
 // elements i = w*EPT .. +EPT-1, element i = (mb, j, e) being row 16*mb + 4*(l/16) + e, column
 // 16*j + l%16 (the MFMA result layout).
 template <int MB, int XR, int WAVES, int R>
-__device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int tile, int ku, int m0,
-                                 const BaseLds<MB, XR, WAVES, R> &lds)
+__device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int pi, int tile, int ku,
+                                 int m0, const BaseLds<MB, XR, WAVES, R> &lds)
 {
     constexpr int ROWS = 16 * MB;
     constexpr int NT = 64 * WAVES;
@@ -362,10 +400,33 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     }
 
     MLORA_TRACE_POINT(trace_slot, 2);
+    const int tiles = tiles_n(N);
+    const int chunk = m0 / ROWS, chunks = a.m_pad / ROWS;
+    // What the epilogue reads from other blocks: one thread waits for their counters, then the
+    // block meets (which also frees the staging buffers) and reads with load_shared.
+    if (ku == 0 && tid == 0) {
+        bool ok = true;
+        if (lora) {
+            ok = wait_count(a.ctrl + CTRL_SHRINK_DONE + pi, (unsigned)P.n_shrink_blocks);
+            // the last finishing block of the projection that gets here resets both counters
+            if (atomicAdd(a.ctrl + CTRL_SHRINK_USED + pi, 1u) + 1u == (unsigned)P.n_finish_blocks) {
+                __hip_atomic_store(a.ctrl + CTRL_SHRINK_DONE + pi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.ctrl + CTRL_SHRINK_USED + pi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (P.ksplit > 1) {
+            unsigned *c = a.ctrl + P.part_ctr + tile * chunks + chunk;
+            ok = wait_count(c, (unsigned)(P.ksplit - 1)) && ok;
+            __hip_atomic_store(c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (!ok) atomicOr(a.status, 1u);
+    }
+    __syncthreads();
+    MLORA_TRACE_POINT(trace_slot, 8);
+
     // split-K partials of this thread's outputs: all requested at once (a thread with nothing to
     // add re-reads a valid address), consumed after the reduction below
     constexpr int PU = 3;
-    const int tiles = tiles_n(N);
     float pv[EPT][PU];
 #pragma unroll
     for (int qq = 0; qq < EPT; ++qq)
@@ -375,10 +436,15 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             const bool ok = ku == 0 && u + 1 < P.ksplit && m < M;
             const float *src = ok ? P.partial + (((size_t)u * tiles + tile) * a.m_pad + m) * TILE_N + elem_col(qq)
                                   : reinterpret_cast<const float *>(P.codes);
-            pv[qq][u] = *src;
+            pv[qq][u] = load_shared(src);
         }
-    // partial tiles -> LDS (over the staging buffers, once every wave is done reading them)
-    __syncthreads();
+    // one entry of t per thread (K-chunk partials of the shrink step, summed in fixed order)
+    float tv[MAX_KCHUNKS];
+    if (fast) {
+#pragma unroll
+        for (int kc = 0; kc < MAX_KCHUNKS; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
+    }
+    // partial tiles -> LDS (over the staging buffers)
     {
         float *red = lds.red(wave);
 #pragma unroll
@@ -391,13 +457,11 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 
     // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
     if (fast) {
-        if constexpr (PREFETCH) {
-            if (pf.t_mine) {
-                float v = 0.f;
+        if (pf.t_mine) {
+            float v = 0.f;
 #pragma unroll
-                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? pf.t[kc] : 0.f;
-                lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
-            }
+            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? tv[kc] : 0.f;
+            lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
         }
     } else if (lora) {
         for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
@@ -406,7 +470,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             float v = 0.f;
             if (ad >= 0 && ad < P.n_adapters)
                 for (int kc = 0; kc < P.kch; ++kc)
-                    v += P.t_part[((size_t)kc * M + (m0 + ml)) * P.r16 + jj];
+                    v += load_shared(P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj);
             lds.t_row(ml)[jj] = v * P.alpha;
         }
     }
@@ -425,7 +489,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         const int m = m0 + ml;
         const int n = tile * TILE_N + col;
         if (ku > 0) {
-            P.partial[(((size_t)(ku - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col] = v;
+            store_shared(P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col, v);
             continue;
         }
         if (m < M && n < N) {
@@ -433,7 +497,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             for (int u = 0; u < PU; ++u)
                 if (u + 1 < P.ksplit) v += pv[qq][u];
             for (int u = PU + 1; u < P.ksplit; ++u)
-                v += P.partial[(((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col];
+                v += load_shared(P.partial + (((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col);
             const int ad = elem_ad(qq);
             if (ad >= 0) {
                 float l = 0.f;
@@ -453,6 +517,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
         }
     }
+    if (ku > 0) signal_done(a.ctrl + P.part_ctr + tile * chunks + chunk);
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
@@ -464,15 +529,18 @@ struct ShrinkLds {
     float red[4][256];
 };
 
-__device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int local, ShrinkLds &lds)
+__device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int pi, int local, ShrinkLds &lds)
 {
     GroupLds &g = lds.g;
+    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    MLORA_TRACE_POINT(trace_slot, 0);
     const int jblocks = P.r16 / 16;
     const int kc = local % P.kch;
     const int jb = (local / P.kch) % jblocks;
     const int ti = local / (P.kch * jblocks);
 
     group_rows_lds(a.row_adapter, a.M, P.n_adapters, g);
+    MLORA_TRACE_POINT(trace_slot, 1);
 
     // locate row tile ti among the segments (16 rows per tile, tiles never straddle segments)
     int seg = -1, first = 0, tiles_before = 0;
@@ -486,7 +554,10 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
         }
         tiles_before += nt;
     }
-    if (seg < 0) return;                                   // uniform over the block
+    if (seg < 0) {                                         // uniform over the block: nothing to do,
+        signal_done(a.ctrl + CTRL_SHRINK_DONE + pi);       // but the finishing blocks count it
+        return;
+    }
     const int adapter = g.seg_adapter[seg];
     const int rows_here = min(16, (int)g.seg_start[seg + 1] - first);
 
@@ -538,9 +609,11 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
                          lds.red[2][e * 64 + lane]) + lds.red[3][e * 64 + lane];
         if (i < rows_here) {
             const int m = g.perm[first + i];
-            P.t_part[((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16] = v;
+            store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16, v);
         }
     }
+    signal_done(a.ctrl + CTRL_SHRINK_DONE + pi);
+    MLORA_TRACE_POINT(trace_slot, 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -591,60 +664,63 @@ __device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH]
 }
 
 template <int MB, int XR>
-__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_pre_kernel(const LayerArgs a)
+__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
     const int b = (int)blockIdx.x;
-    if (b < a.pre_base_blocks) {
-        const BaseLdsOf<MB, XR> lds{smem};
-        int first;
-        const int pi = find_proj(a.pre_begin, b, first);
-        const ProjArgs P = fetch_proj(a, pi);
-        const int local = b - first;
-        const int tiles = tiles_n(P.N);
-        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, local % tiles, 1 + local / tiles,
-                                                              (int)blockIdx.y * 16 * MB, lds);
-    } else {
+    int first;
+    if (b < a.shrink_blocks) {
         if (blockIdx.y != 0) return;
-        const int sb = b - a.pre_base_blocks;
-        int first;
-        const int pi = find_proj(a.shrink_begin, sb, first);
-        shrink_block(a, fetch_proj(a, pi), sb - first, *reinterpret_cast<ShrinkLds *>(smem));
+        const int pi = find_proj(a.shrink_begin, b, first);
+        shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        return;
+    }
+    const BaseLdsOf<MB, XR> lds{smem};
+    const int m0 = (int)blockIdx.y * 16 * MB;
+    if (b < a.shrink_blocks + a.pre_base_blocks) {
+        const int pb = b - a.shrink_blocks;
+        const int pi = find_proj(a.pre_begin, pb, first);
+        const ProjArgs P = fetch_proj(a, pi);
+        const int local = pb - first;
+        const int tiles = tiles_n(P.N);
+        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, local % tiles, 1 + local / tiles, m0, lds);
+    } else {
+        const int mb_ = b - a.shrink_blocks - a.pre_base_blocks;
+        const int pi = find_proj(a.main_begin, mb_, first);
+        const ProjArgs P = fetch_proj(a, pi);
+        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, mb_ - first, 0, m0, lds);
     }
 }
 
 template <int MB, int XR>
-__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_main_kernel(const LayerArgs a)
-{
-    __shared__ __align__(16) unsigned char smem[BaseLdsOf<MB, XR>::BYTES];
-    const BaseLdsOf<MB, XR> lds{smem};
-    const int b = (int)blockIdx.x;
-    int first;
-    const int pi = find_proj(a.main_begin, b, first);
-    const ProjArgs P = fetch_proj(a, pi);
-    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, b - first, 0,
-                                                          (int)blockIdx.y * 16 * MB, lds);
-}
-
-template <int MB, int XR>
-static hipError_t launch_both(const LayerArgs &a, int n_blocks, bool pre, hipStream_t s)
+static hipError_t launch_instance(const LayerArgs &a, int n_blocks, hipStream_t s)
 {
     const dim3 grid((unsigned)n_blocks, (unsigned)(a.m_pad / rows_per_chunk(a.M)));
-    const dim3 block(64 * Shape<MB>::WAVES);
-    if (pre) layer_pre_kernel<MB, XR><<<grid, block, 0, s>>>(a);
-    else     layer_main_kernel<MB, XR><<<grid, block, 0, s>>>(a);
+    layer_kernel<MB, XR><<<grid, dim3(64 * Shape<MB>::WAVES), 0, s>>>(a);
     return hipGetLastError();
 }
 
-static hipError_t launch_layer(const LayerArgs &a, int n_blocks, bool pre, hipStream_t s)
+hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s)
 {
-    if (a.M <= 8)  return launch_both<1, 8>(a, n_blocks, pre, s);
-    if (a.M <= 16) return launch_both<1, 16>(a, n_blocks, pre, s);
-    if (a.M <= 24) return launch_both<2, 24>(a, n_blocks, pre, s);
-    return launch_both<2, 32>(a, n_blocks, pre, s);
+    if (a.M <= 8)  return launch_instance<1, 8>(a, n_blocks, s);
+    if (a.M <= 16) return launch_instance<1, 16>(a, n_blocks, s);
+    if (a.M <= 24) return launch_instance<2, 24>(a, n_blocks, s);
+    return launch_instance<2, 32>(a, n_blocks, s);
 }
 
-hipError_t launch_pre(const LayerArgs &a, int n_blocks, hipStream_t s) { return launch_layer(a, n_blocks, true, s); }
-hipError_t launch_main(const LayerArgs &a, int n_blocks, hipStream_t s) { return launch_layer(a, n_blocks, false, s); }
+__global__ void zero_kernel(uint4 *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_zero(void *p, size_t bytes, hipStream_t s)
+{
+    const size_t n = bytes / 16;
+    if (n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    zero_kernel<<<dim3(blocks), dim3(256), 0, s>>>(reinterpret_cast<uint4 *>(p), n);
+    return hipGetLastError();
+}
 
 }  // namespace mlora

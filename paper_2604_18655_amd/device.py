@@ -48,4 +48,6 @@ def y_to_numpy(y: torch.Tensor) -> np.ndarray:
 
 def alloc_workspace(projs, M: int, device="cuda:0") -> torch.Tensor:
     n = max(binding.workspace_bytes(projs, M), 256)
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    binding.workspace_init(ws)              # completion counters start at zero
+    return ws

@@ -33,6 +33,23 @@ def random_problem(seed, K, N, G, r, n_ad):
     return wl.make_problem(shape, 900 + seed, 0, 0)
 
 
+def control_bytes(shapes, M):
+    """Size of the status word + completion counters at the head of a workspace (one launch of
+    up to 16 projections): 32 fixed counters and one per (column tile, row chunk) of every
+    projection whose K is cut into more than one unit of 2048 inputs."""
+    rpc = 16 if M <= 16 else 32
+    chunks = -(-M // rpc)
+    n = sum(-(-s.N // 64) * chunks for s in shapes if -(-(s.K // 128) // 16) > 1)
+    return 256 + -(-(32 + n) * 4 // 256) * 256
+
+
+def assert_workspace_clean(ws, shapes, M):
+    """After a call the status word is 0 (no block gave up waiting) and every counter is back
+    at 0, so the next call can use the workspace as it is."""
+    n = min(control_bytes(shapes, M), ws.numel())
+    assert int(ws[:n].count_nonzero().item()) == 0, "status word or completion counters not zero"
+
+
 def run_linear(gpu, prob, x_bits, rows, y_dtype):
     lib, device, torch = gpu
     proj = device.upload_problem(prob)
@@ -43,6 +60,8 @@ def run_linear(gpu, prob, x_bits, rows, y_dtype):
     ws = device.alloc_workspace([proj], max(M, 1))
     lib.linear(proj, x, ra, M, y, y_dtype, ws)
     torch.cuda.synchronize()
+    if M > 0:
+        assert_workspace_clean(ws, [prob.shape], M)
     return device.y_to_numpy(y)
 
 
@@ -214,7 +233,58 @@ def layer_on_gpu(gpu, probs, xs, rows, y_dtype):
     ws = device.alloc_workspace(projs, M)
     lib.layer_step(projs, dxs, ys, ra, M, y_dtype, ws)
     torch.cuda.synchronize()
+    assert_workspace_clean(ws, [p.shape for p in probs], M)
     return [device.y_to_numpy(y) for y in ys]
+
+
+def test_workspace_reuse_and_graph_replay_match_first_call(gpu):
+    """One workspace serves call after call (the counters reset themselves), eagerly and as a
+    captured graph replayed several times with eager work in between: every result equals the
+    first call's bit for bit."""
+    lib, device, torch = gpu
+    w = wl.WORKLOADS["c2"]
+    probs, xs, rows = wl.make_layer(w, layer=1)
+    projs = [device.upload_problem(p) for p in probs]
+    cache, dxs = {}, []
+    for x in xs:
+        if id(x) not in cache:
+            cache[id(x)] = device.to_device(x)
+        dxs.append(cache[id(x)])
+    M = w.M
+    ra = torch.from_numpy(rows).cuda()
+    ys = [device.alloc_y(M, p.shape.N, lib.Y_BF16) for p in probs]
+    ws = device.alloc_workspace(projs, M)
+    plan = lib.LayerPlan(projs, dxs, ys, ra, M, lib.Y_BF16, ws)
+
+    def snapshot_and_clobber():
+        torch.cuda.synchronize()
+        assert_workspace_clean(ws, [p.shape for p in probs], M)
+        out = [y.clone() for y in ys]
+        for y in ys:
+            y.fill_(-1)
+        return out
+
+    plan.run()
+    first = snapshot_and_clobber()
+    for _ in range(3):
+        plan.run()
+        again = snapshot_and_clobber()
+        assert all(torch.equal(a, b) for a, b in zip(first, again))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            plan.run(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(4):
+        graph.replay()
+        again = snapshot_and_clobber()
+        assert all(torch.equal(a, b) for a, b in zip(first, again)), f"replay {i}"
+        plan.run()                                   # eager work between replays
+        again = snapshot_and_clobber()
+        assert all(torch.equal(a, b) for a, b in zip(first, again))
 
 
 def test_config2_layer_step_all_projections(gpu):
