@@ -36,7 +36,7 @@ mlora_status check_proj(const mlora_w4_proj &p)
 int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 16 * 16 : 0; }
 int kch_of(const mlora_w4_proj &p)
 {
-    int c = p.K / 512;   // at least 512 inputs per chunk, at most MAX_KCHUNKS chunks
+    int c = p.K / 1024;  // 1024 inputs per chunk (8 k-steps per wave, requested at once), at most MAX_KCHUNKS chunks
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 size_t t_part_bytes(const mlora_w4_proj &p, int M)
@@ -125,7 +125,7 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
 // Counters exist only if something is shared between blocks (LoRA or split-K).
 static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M, bool lora)
 {
-    size_t n = 0;
+    size_t n = 0;                              // counter lines of the split-K tiles
     bool any = false;
     for (int i = 0; i < count; ++i) {
         if (ksplit_of(projs[i]) > 1) {
@@ -134,7 +134,7 @@ static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M,
         }
         any = any || (lora && projs[i].n_adapters > 0);
     }
-    return any ? round_up((CTRL_PART + n) * sizeof(unsigned), 256) : 0;
+    return any ? (CTRL_PART + n * CTR_STRIDE) * sizeof(unsigned) : 0;
 }
 
 static size_t ctrl_bytes_total(const mlora_w4_proj *projs, int n_proj, int M, bool lora)
@@ -234,7 +234,7 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             d.partial = reinterpret_cast<float *>(ws);
             ws += partial_bytes(p, M);
             d.part_ctr = part_ctr;
-            if (d.ksplit > 1) part_ctr += tiles_n(p.N) * chunks;
+            if (d.ksplit > 1) part_ctr += tiles_n(p.N) * chunks * CTR_STRIDE;
             a.shrink_begin[i] = shrink_blocks;
             if (any_lora && p.n_adapters > 0) {
                 d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);

@@ -55,7 +55,7 @@ __host__ __device__ inline uint32_t rotr32(uint32_t v, int s) { return rotl32(v,
 // ---------------------------------------------------------------------------------------------
 constexpr int MAX_PROJ_PER_LAUNCH = 16;
 constexpr int ROWS_PER_BLOCK16 = 16;
-constexpr int MAX_KCHUNKS = 4;     // partial sums of the shrink step the epilogue adds up
+constexpr int MAX_KCHUNKS = 16;    // partial sums of the shrink step the epilogue adds up
 
 struct ProjArgs {
     const uint4 *codes;        // blob, code region
@@ -75,14 +75,21 @@ struct ProjArgs {
     int ksplit;                // K units per tile; unit 0 finishes the tile, the others run ahead
     int n_shrink_blocks;       // shrink blocks of this projection (each bumps its counter once)
     int n_finish_blocks;       // finishing blocks of this projection (tiles x row chunks)
-    int part_ctr;              // index of this projection's first split-K counter in ctrl
+    int part_ctr;              // index of this projection's first split-K counter line in ctrl
 };
 
-// Counters in the workspace that order the blocks of one launch (all zero between calls):
-//   ctrl[p]            shrink blocks of projection p that have finished
-//   ctrl[16 + p]       finishing blocks of projection p that have seen them all (the last resets both)
-//   ctrl[part_ctr + tile * chunks + chunk]   split-K units of that tile that have finished
-constexpr int CTRL_SHRINK_DONE = 0, CTRL_SHRINK_USED = MAX_PROJ_PER_LAUNCH, CTRL_PART = 2 * MAX_PROJ_PER_LAUNCH;
+// Counters in the workspace that order the blocks of one launch (all zero between calls).
+// Every counter has a 128-byte line of its own, and what many blocks wait for exists in
+// CTR_REPL copies, each polled by a share of the waiting blocks: hundreds of blocks polling one
+// line queue up behind each other in one memory channel, and since a wave's loads return in
+// order that stalls their weight streams too.
+//   shrink_ctr(p, r)      + 0: shrink blocks of projection p that have finished (copy r)
+//                         + 1: finishing blocks that have used copy r (the last one resets both)
+//   part_ctr + (tile * chunks + chunk) * CTR_STRIDE: split-K units of that tile that have finished
+constexpr int CTR_REPL = 16;
+constexpr int CTR_STRIDE = 32;                 // uint32 per counter line
+__host__ __device__ inline int shrink_ctr(int p, int r) { return (p * CTR_REPL + r) * CTR_STRIDE; }
+constexpr int CTRL_PART = MAX_PROJ_PER_LAUNCH * CTR_REPL * CTR_STRIDE;
 constexpr size_t WS_HEADER_BYTES = 256;        // status word at the front of every workspace
 
 struct LayerArgs {

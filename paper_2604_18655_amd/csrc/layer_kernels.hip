@@ -54,12 +54,12 @@ __device__ __forceinline__ float load_shared(const float *p)
 }
 
 // all threads of the block, after their store_shared calls: wait until the own stores have been
-// acknowledged, meet, then count the block as done
-__device__ __forceinline__ void signal_done(unsigned *counter)
+// acknowledged, meet, then count the block as done in `copies` counter lines
+__device__ __forceinline__ void signal_done(unsigned *counter, int copies)
 {
     __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): every store of this wave has completed
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(counter, 1u);
+    if ((int)threadIdx.x < copies) atomicAdd(counter + threadIdx.x * CTR_STRIDE, 1u);
 }
 
 // one thread: wait until *counter has reached expected; false if the wait ran out
@@ -224,12 +224,116 @@ __device__ __forceinline__ void round_compute(f32x4 (&acc)[MB][4], const unsigne
     }
 }
 
-// Loads the epilogue needs, issued from inside the K loop (all unconditional; a thread with
-// nothing to fetch re-reads a valid address).
+// ------------------------------------------------------------------------------------------
+// Decode shapes (at most 16 rows per chunk): a wave has at most 16 k-steps, so there is no
+// steady state to speak of and the K loop is a register pipeline instead of rounds.  The rows
+// of x for the wave's whole range go to a wave-private LDS buffer once; the packed codes stay
+// in registers, four k-steps deep, and each k-step's register is refilled as soon as it has
+// been consumed.  Little state per wave (4 KiB of codes in flight, under 128 registers) lets
+// four blocks share a compute unit, so every block of a decoder layer is resident at once and
+// the bytes in flight come from the number of waves rather than from the depth of each.
+// ------------------------------------------------------------------------------------------
+template <int XR>
+struct StreamLds {
+    static constexpr int XSTEPS = UNIT_SUPER_STEPS;            // k-steps per wave: (16 super-steps x 4) / 4 waves
+    static constexpr int XROW = XSTEPS * 64 + 16;              // bytes of a row of x; +16: rows 4 banks apart
+    static constexpr int BYTES = XR * XROW;                    // per wave
+};
+
+// Codes and scales of one super-step (four k-steps); a wave keeps two of them in flight.
+struct StreamRegs {
+    u32x4 w[4];
+    uint2 sc[4];                                               // one per scale group of the super-step
+};
+
+// Request super-step `ss` of the wave (wp0/sp0 = the wave's first chunk / first group WITHOUT the
+// lane's offset).  A request past the wave's range (ss >= n_ss) becomes one 16-byte read of the
+// first chunk by all lanes: every load stays unconditional, so the waits the compiler derives
+// stay exact, and the useless ones cost next to nothing.
+__device__ __forceinline__ void stream_request(StreamRegs &r, const u32x4 *wp0, const uint2 *sp0, int ss, int n_ss,
+                                               int gs, int lane)
+{
+    const bool in = ss < n_ss;
+    const u32x4 *wn = wp0 + (in ? (size_t)ss * 256 + lane : 0);
+    const uint2 *sn = sp0 + (in ? (size_t)ss * gs * 16 + (lane & 15) : 0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) r.w[u] = wn[in ? u * 64 : 0];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) r.sc[g] = sn[in ? min(g, gs - 1) * 16 : 0];
+}
+
+// The math of one super-step; xs = this lane's row of x in LDS at the super-step's first k-step.
+template <int SPG>
+__device__ __forceinline__ void stream_math(f32x4 (&acc)[4], const StreamRegs &r, const unsigned char *xs,
+                                            uint32_t mask, uint32_t bias)
+{
+    constexpr int GS = 4 / SPG;                                // scale groups per super-step
+    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
+#pragma unroll
+    for (int g = 0; g < GS; ++g) {
+        uint4 xa[SPG];
+        f32x4 corr = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < SPG; ++t) {
+            xa[t] = *reinterpret_cast<const uint4 *>(xs + (g * SPG + t) * 64);
+            corr = mfma16(xa[t], neg24, corr);                 // -24 * sum of x: cancels the code offset
+        }
+        f32x4 d[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            d[j] = corr;
+#pragma unroll
+            for (int t = 0; t < SPG; ++t) {
+                const u32x4 wv = r.w[g * SPG + t];
+                const uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
+                d[j] = mfma16(xa[t], expand_codes(wj, mask, bias), d[j]);
+            }
+        }
+        const uint2 sv = r.sc[g];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
+                           : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(d[j][e], sj, acc[j][e]);
+        }
+    }
+}
+
+// n_ss super-steps (at most 4), two per pass: set A holds the even ones, set B the odd ones, and
+// each set is requested again (two super-steps ahead) as soon as it has been consumed.  xl = this
+// lane's row of x in LDS (+ 16 * (lane/16)).  During the last pass the wave also reads the two
+// completion counters its epilogue depends on (poll_s, poll_p; before that, and for a wave that
+// depends on nothing, a dummy address): if they are complete by then, the epilogue need not wait
+// for a poll of its own.
+template <int SPG>
+__device__ __forceinline__ void stream_loop(f32x4 (&acc)[4], StreamRegs &ra, StreamRegs &rb, const u32x4 *wp0,
+                                            const uint2 *sp0, int n_ss, const unsigned char *xl, uint32_t mask,
+                                            uint32_t bias, int lane, const unsigned *poll_s, const unsigned *poll_p,
+                                            unsigned &seen_s, unsigned &seen_p)
+{
+    constexpr int GS = 4 / SPG;
+    const unsigned *dummy = reinterpret_cast<const unsigned *>(wp0);
+#pragma nounroll
+    for (int ss = 0; ss < n_ss; ss += 2) {
+        const bool last = ss + 2 >= n_ss;
+        seen_s = __hip_atomic_load(last ? poll_s : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        seen_p = __hip_atomic_load(last ? poll_p : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        stream_math<SPG>(acc, ra, xl + ss * 256, mask, bias);
+        stream_request(ra, wp0, sp0, ss + 2, n_ss, GS, lane);
+        if (ss + 1 < n_ss) stream_math<SPG>(acc, rb, xl + (ss + 1) * 256, mask, bias);
+        stream_request(rb, wp0, sp0, ss + 3, n_ss, GS, lane);
+    }
+}
+
+// Loads the epilogue needs that do not depend on other blocks, requested ahead of their use (all
+// unconditional; a thread with nothing to fetch re-reads a valid address).  The N outputs of a
+// thread lie in one row, 16 columns apart, so their rows of B differ by a fixed stride.
 template <int N>
 struct EpiPrefetch {
-    const uint16_t *brow[N > 0 ? N : 1];     // row of B per output (or a safe address)
-    int bstep[N > 0 ? N : 1];                // rank - 8 (offset of the last 8 ranks), or 0
+    const uint16_t *bad;                     // B of the row's adapter (or a safe address)
+    int brank;                               // rank (0 with the safe address: every offset is 0)
+    int n0, nlast;                           // column of output 0; last valid column
     const float *tp;                         // this thread's entry of t_part[0] (or a safe address)
     size_t tstride;                          // distance between K chunks of t_part
     int kch, t_ml, t_jj;
@@ -237,33 +341,44 @@ struct EpiPrefetch {
     uint4 b[N > 0 ? N : 1][2];
     __device__ __forceinline__ void issue()
     {
-        // the addresses pass through an empty asm: without it the compiler hoists these loads to
+        // the address passes through an empty asm: without it the compiler hoists these loads to
         // the top of the kernel and then spills their results across the whole K loop
-#pragma unroll
-        for (int q = 0; q < N; ++q) asm volatile("" : "+v"(brow[q]));
+        asm volatile("" : "+v"(bad));
+        const int second = brank > 8 ? 8 : 0;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            b[q][0] = *reinterpret_cast<const uint4 *>(brow[q]);
-            b[q][1] = *reinterpret_cast<const uint4 *>(brow[q] + min(8, bstep[q]));
+            const uint16_t *row = bad + (unsigned)(min(n0 + 16 * q, nlast) * brank);
+            b[q][0] = *reinterpret_cast<const uint4 *>(row);
+            b[q][1] = *reinterpret_cast<const uint4 *>(row + second);
         }
     }
 };
 
 constexpr int FAST_RANK = 16;                  // the epilogue prefetch covers ranks up to this
 
-// LDS of a base block: the per-wave staging buffers; after the K loop the same memory holds the
-// per-wave partial tiles and alpha * t of the chunk's rows.
+// LDS of a base block: the per-wave staging buffers, the per-wave partial tiles (red) and
+// alpha * t of the chunk's rows.  Decode shapes: a wave's partial tile lies over its OWN staging
+// buffer and t has room of its own, so a wave that is done with its K loop need not wait for the
+// others before it writes either.  Above 16 rows red and t lie over the staging buffers of all
+// waves and the block meets first.
 template <int MB, int XR, int WAVES, int R>
 struct BaseLds {
-    static constexpr int STAGE_BYTES = WAVES * RoundLds<XR, R>::BYTES;
-    static constexpr int RED_BYTES = WAVES * MB * 1024 * 4;
+    static constexpr bool PRIVATE = MB == 1;
+    static constexpr int WAVE_STAGE = PRIVATE ? StreamLds<XR>::BYTES : RoundLds<XR, R>::BYTES;
+    static constexpr int STAGE_BYTES = WAVES * WAVE_STAGE;
+    static constexpr int RED_WAVE = MB * 1024 * 4;             // bytes of one wave's partial tile
     static constexpr int TS_STRIDE = MLORA_MAX_RANK + 4;
-    static constexpr int TS_BYTES = 16 * MB * TS_STRIDE * 4;
-    static constexpr int BYTES = STAGE_BYTES > RED_BYTES + TS_BYTES ? STAGE_BYTES : RED_BYTES + TS_BYTES;
+    static constexpr int TS_BYTES = (PRIVATE ? XR : 16 * MB) * TS_STRIDE * 4;
+    static constexpr int T_AT = PRIVATE ? STAGE_BYTES : WAVES * RED_WAVE;
+    static constexpr int BYTES = T_AT + TS_BYTES > STAGE_BYTES ? T_AT + TS_BYTES : STAGE_BYTES;
+    static_assert(!PRIVATE || WAVE_STAGE >= RED_WAVE, "a wave's partial tile must fit its own staging buffer");
     unsigned char *base;
-    __device__ unsigned char *stage(int wave) const { return base + wave * RoundLds<XR, R>::BYTES; }
-    __device__ float *red(int wave) const { return reinterpret_cast<float *>(base) + wave * MB * 1024; }
-    __device__ float *t_row(int ml) const { return reinterpret_cast<float *>(base + RED_BYTES) + ml * TS_STRIDE; }
+    __device__ unsigned char *stage(int wave) const { return base + wave * WAVE_STAGE; }
+    __device__ float *red(int wave) const
+    {
+        return reinterpret_cast<float *>(base + wave * (PRIVATE ? WAVE_STAGE : RED_WAVE));
+    }
+    __device__ float *t_row(int ml) const { return reinterpret_cast<float *>(base + T_AT) + ml * TS_STRIDE; }
 };
 
 __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
@@ -280,9 +395,10 @@ __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
 }
 
 // ku == 0: finish the tile (add split-K partials, LoRA term, store y); ku > 0: leave a partial.
-// WAVES waves split the unit's super-steps; thread (wave w, lane l) then finishes the EPT tile
-// elements i = w*EPT .. +EPT-1, element i = (mb, j, e) being row 16*mb + 4*(l/16) + e, column
-// 16*j + l%16 (the MFMA result layout).
+// WAVES (= 4) waves split the unit's super-steps.  In the MFMA result layout lane l holds, for
+// row block mb and column block j, the rows 16*mb + 4*(l/16) + e (e = 0..3) of column 16*j + l%16;
+// thread (wave w, lane l) finishes e = w of every (mb, j): EPT = 4*MB outputs that lie in MB rows
+// (one adapter each), 16 columns apart.
 template <int MB, int XR, int WAVES, int R>
 __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int pi, int tile, int ku,
                                  int m0, const BaseLds<MB, XR, WAVES, R> &lds)
@@ -291,8 +407,8 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     constexpr int NT = 64 * WAVES;
     constexpr int EPT = MB * 16 / WAVES;
     const int K = P.K, N = P.N, M = a.M;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, lq = lane >> 4;
+    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int l16 = lane & 15, lq = lane >> 4;
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * WAVES + wave;
     MLORA_TRACE_POINT(trace_slot, 0);
 
@@ -316,13 +432,14 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     constexpr bool PREFETCH = EPT <= 4;                    // more outputs per thread: too many registers
     const bool fast = PREFETCH && lora && P.rank <= FAST_RANK && rows_here * P.r16 <= NT;
     // element qq of this thread: tile row and column (cheap to recompute, so not kept live)
-    auto elem_ml = [&](int qq) { const int i = wave * EPT + qq; return (i >> 4) * 16 + 4 * lq + (i & 3); };
-    auto elem_col = [&](int qq) { const int i = wave * EPT + qq; return 16 * ((i >> 2) & 3) + l16; };
+    static_assert(WAVES == 4, "one wave per element of an MFMA result register");
+    auto elem_ml = [&](int qq) { return (qq >> 2) * 16 + 4 * lq + wave; };
+    auto elem_col = [&](int qq) { return 16 * (qq & 3) + l16; };
     const int *ra_safe = lora ? a.row_adapter : reinterpret_cast<const int *>(P.codes);
     const int ra_last = lora ? M - 1 : 0;
-    int ad_raw[EPT];
+    int ad_raw[MB];                                        // as loaded, one per row of this thread
     auto elem_ad = [&](int qq) {
-        const int v = ad_raw[qq];
+        const int v = ad_raw[qq >> 2];
         return (lora && m0 + elem_ml(qq) < M && v >= 0 && v < P.n_adapters) ? v : -1;
     };
 
@@ -337,17 +454,16 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     // thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
     EpiPrefetch<PREFETCH ? EPT : 0> pf;
     auto prefetch_setup = [&]() {
-        pf.t_ml = tid / max(P.r16, 1);
-        pf.t_jj = tid % max(P.r16, 1);
+        pf.t_ml = tid >> 4;                                // (fast: r16 == 16)
+        pf.t_jj = tid & 15;
         pf.t_mine = fast && tid < rows_here * P.r16;
-        const uint16_t *safe = reinterpret_cast<const uint16_t *>(P.codes);
-#pragma unroll
-        for (int qq = 0; qq < (PREFETCH ? EPT : 0); ++qq) {
-            const int n = tile * TILE_N + elem_col(qq);
-            const int ad = elem_ad(qq);
-            const bool ok = fast && ad >= 0 && n < N;
-            pf.brow[qq] = ok ? P.lora_b + ((size_t)ad * N + n) * P.rank : safe;
-            pf.bstep[qq] = ok ? P.rank - 8 : 0;
+        {
+            const int ad = elem_ad(0);                     // (PREFETCH: one row per thread)
+            const bool ok = fast && ad >= 0;
+            pf.bad = ok ? P.lora_b + (size_t)ad * N * P.rank : reinterpret_cast<const uint16_t *>(P.codes);
+            pf.brank = ok ? P.rank : 0;
+            pf.n0 = tile * TILE_N + l16;
+            pf.nlast = N - 1;
         }
         pf.tp = pf.t_mine ? P.t_part + (size_t)(m0 + pf.t_ml) * P.r16 + pf.t_jj
                           : reinterpret_cast<const float *>(P.codes);
@@ -361,163 +477,296 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     uint32_t bias = a.code_bias;
     asm volatile("" : "+v"(bias));      // pin to a vector register (one scalar operand per op)
 
-    // K loop: pairs of rounds.  An idle wave (my_cnt == 0) still requests one pair at a valid
-    // place and computes nothing.
+    // counters this block depends on (or signals): see common.hpp
+    const int tiles = tiles_n(N);
+    const int chunk = m0 / ROWS, chunks = a.m_pad / ROWS;
+    const int fin = tile * chunks + chunk;                 // this finishing block among its projection's
+    const int copies = min(CTR_REPL, P.n_finish_blocks);   // copies of the shrink counter in use
+    unsigned *const sctr = a.ctrl + shrink_ctr(pi, fin % copies);
+    unsigned *const pctr = a.ctrl + P.part_ctr + fin * CTR_STRIDE;
+    const bool need_s = lora, need_p = ku == 0 && P.ksplit > 1;
+    unsigned seen_s = 0, seen_p = 0;                       // what an early look at them showed
+
     unsigned char *buf = lds.stage(wave);
     const int ks_first = my_beg * 4, ks_total = my_cnt * 4;
     const int rows_x = min(rows_here, XR);
-    for (int r0 = 0; r0 < max(ks_total, 1); r0 += 2 * R) {
-        RoundRegs<XR, R> ra, rb;
-        round_issue_w<XR, R>(ra, codes_tile, ks_first + r0, lane);
-        round_issue_xs<XR, R>(ra, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0, lane);
-        round_issue_w<XR, R>(rb, codes_tile, ks_first + r0 + R, lane);
-        round_issue_xs<XR, R>(rb, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0 + R, lane);
-        // adapters of this thread's rows: requested here (unconditionally), decoded when needed
+    if constexpr (MB == 1) {
+        // decode shapes: rows of x of the wave's whole range -> LDS, then the register pipeline
+        using L = StreamLds<XR>;
+        u32x4 xr[XR];
+        const int kx = min(ks_first * KSTEP + lane * 8, K - 8);
 #pragma unroll
-        for (int qq = 0; qq < EPT; ++qq) ad_raw[qq] = ra_safe[min(m0 + elem_ml(qq), ra_last)];
-        // keep the second round's requests ahead of the first wait: the scheduler would
-        // otherwise sink them below it to save registers, which halves the bytes in flight
-        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < XR; ++i)
+            xr[i] = *reinterpret_cast<const u32x4 *>(P.x + (size_t)(m0 + min(i, rows_x - 1)) * K + kx);
+        // adapters of this thread's rows: requested here (unconditionally), decoded below
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) ad_raw[mb] = ra_safe[min(m0 + elem_ml(4 * mb), ra_last)];
+        const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (size_t)ks_first * 64;
+        const uint2 *sp = scales_tile + (size_t)(ks_first / P.spg) * 16;
+        const unsigned char *xl = buf + min(l16, rows_x - 1) * L::XROW + 16 * lq;
+        StreamRegs sa, sb;
+        // an idle wave requests (and ignores) the unit's first super-step
+        stream_request(sa, wp, sp, 0, max(my_cnt, 1), 4 / P.spg, lane);
+        stream_request(sb, wp, sp, 1, my_cnt, 4 / P.spg, lane);
+        __builtin_amdgcn_sched_barrier(0);                     // (the requests stay ahead of the wait for x)
+#pragma unroll
+        for (int i = 0; i < XR; ++i) *reinterpret_cast<u32x4 *>(buf + lane * 16 + i * L::XROW) = xr[i];
+        const unsigned *dummy = reinterpret_cast<const unsigned *>(wp);
+        const unsigned *poll_s = need_s ? sctr : dummy, *poll_p = need_p ? pctr : dummy;
         MLORA_TRACE_POINT(trace_slot, 7);
-        const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
-        round_to_lds<XR, R>(ra, buf, lane);
-        // epilogue operands: requested as soon as the first round's registers are free, in
-        // flight while both rounds are computed.  (The empty asm keeps the decoding of the
-        // adapter indices, and with it the wait for their loads, from being hoisted.)
+        if (P.spg == 1)      stream_loop<1>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
+        else if (P.spg == 2) stream_loop<2>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
+        else                 stream_loop<4>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
+        MLORA_TRACE_POINT(trace_slot, 6);
+        // Everything below derives its indices afresh from the thread id: values shared with the
+        // code above the loop would have to live across it, in registers the loop needs.
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+        // rows of B: in flight during what follows.  (The empty asm keeps the decoding of the
+        // adapter index, and with it state that would live across the loop, behind the loop.)
 #pragma unroll
-        for (int qq = 0; qq < EPT; ++qq) asm volatile("" : "+v"(ad_raw[qq]));
+        for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(ad_raw[mb]));
         prefetch_setup();
         pf.issue();
-        __builtin_amdgcn_sched_barrier(0);
-        if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, na, rows_x, mask, bias, lane);
-        else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, na, rows_x, mask, bias, lane);
-        else                 round_compute<MB, XR, R, 4>(acc, buf, na, rows_x, mask, bias, lane);
-        MLORA_TRACE_POINT(trace_slot, 6);
-        round_to_lds<XR, R>(rb, buf, lane);
-        if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, nb, rows_x, mask, bias, lane);
-        else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, nb, rows_x, mask, bias, lane);
-        else                 round_compute<MB, XR, R, 4>(acc, buf, nb, rows_x, mask, bias, lane);
+    } else {
+        // K loop: pairs of rounds.  An idle wave (my_cnt == 0) still requests one pair at a valid
+        // place and computes nothing.
+        for (int r0 = 0; r0 < max(ks_total, 1); r0 += 2 * R) {
+            RoundRegs<XR, R> ra, rb;
+            round_issue_w<XR, R>(ra, codes_tile, ks_first + r0, lane);
+            round_issue_xs<XR, R>(ra, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0, lane);
+            round_issue_w<XR, R>(rb, codes_tile, ks_first + r0 + R, lane);
+            round_issue_xs<XR, R>(rb, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0 + R, lane);
+            // adapters of this thread's rows: requested here (unconditionally), decoded when needed
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) ad_raw[mb] = ra_safe[min(m0 + elem_ml(4 * mb), ra_last)];
+            // keep the second round's requests ahead of the first wait: the scheduler would
+            // otherwise sink them below it to save registers, which halves the bytes in flight
+            __builtin_amdgcn_sched_barrier(0);
+            MLORA_TRACE_POINT(trace_slot, 7);
+            const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
+            round_to_lds<XR, R>(ra, buf, lane);
+            // epilogue operands: requested as soon as the first round's registers are free, in
+            // flight while both rounds are computed.  (The empty asm keeps the decoding of the
+            // adapter indices, and with it the wait for their loads, from being hoisted.)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(ad_raw[mb]));
+            prefetch_setup();
+            pf.issue();
+            __builtin_amdgcn_sched_barrier(0);
+            if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, na, rows_x, mask, bias, lane);
+            else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, na, rows_x, mask, bias, lane);
+            else                 round_compute<MB, XR, R, 4>(acc, buf, na, rows_x, mask, bias, lane);
+            MLORA_TRACE_POINT(trace_slot, 6);
+            round_to_lds<XR, R>(rb, buf, lane);
+            if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, nb, rows_x, mask, bias, lane);
+            else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, nb, rows_x, mask, bias, lane);
+            else                 round_compute<MB, XR, R, 4>(acc, buf, nb, rows_x, mask, bias, lane);
+        }
     }
 
     MLORA_TRACE_POINT(trace_slot, 2);
-    const int tiles = tiles_n(N);
-    const int chunk = m0 / ROWS, chunks = a.m_pad / ROWS;
-    // What the epilogue reads from other blocks: one thread waits for their counters, then the
-    // block meets (which also frees the staging buffers) and reads with load_shared.
-    if (ku == 0 && tid == 0) {
+    // Above 16 rows the partial tiles and t lie over the staging buffers of all waves: meet first.
+    if constexpr (!BaseLds<MB, XR, WAVES, R>::PRIVATE) __syncthreads();
+    // What the epilogue reads from other blocks.  Every wave makes sure of it for itself (all
+    // lanes poll the same word), unless the look during its last super-step already showed it.
+    {
         bool ok = true;
-        if (lora) {
-            ok = wait_count(a.ctrl + CTRL_SHRINK_DONE + pi, (unsigned)P.n_shrink_blocks);
-            // the last finishing block of the projection that gets here resets both counters
-            if (atomicAdd(a.ctrl + CTRL_SHRINK_USED + pi, 1u) + 1u == (unsigned)P.n_finish_blocks) {
-                __hip_atomic_store(a.ctrl + CTRL_SHRINK_DONE + pi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.ctrl + CTRL_SHRINK_USED + pi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        if (P.ksplit > 1) {
-            unsigned *c = a.ctrl + P.part_ctr + tile * chunks + chunk;
-            ok = wait_count(c, (unsigned)(P.ksplit - 1)) && ok;
-            __hip_atomic_store(c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (!ok) atomicOr(a.status, 1u);
+        if (need_s && seen_s < (unsigned)P.n_shrink_blocks) ok = wait_count(sctr, (unsigned)P.n_shrink_blocks);
+        if (need_p && seen_p < (unsigned)(P.ksplit - 1)) ok = wait_count(pctr, (unsigned)(P.ksplit - 1)) && ok;
+        if (!ok && lane == 0) atomicOr(a.status, 1u);
     }
-    __syncthreads();
     MLORA_TRACE_POINT(trace_slot, 8);
 
-    // split-K partials of this thread's outputs: all requested at once (a thread with nothing to
-    // add re-reads a valid address), consumed after the reduction below
-    constexpr int PU = 3;
-    float pv[EPT][PU];
-#pragma unroll
-    for (int qq = 0; qq < EPT; ++qq)
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int m = m0 + elem_ml(qq);
-            const bool ok = ku == 0 && u + 1 < P.ksplit && m < M;
-            const float *src = ok ? P.partial + (((size_t)u * tiles + tile) * a.m_pad + m) * TILE_N + elem_col(qq)
-                                  : reinterpret_cast<const float *>(P.codes);
-            pv[qq][u] = load_shared(src);
-        }
-    // one entry of t per thread (K-chunk partials of the shrink step, summed in fixed order)
-    float tv[MAX_KCHUNKS];
-    if (fast) {
-#pragma unroll
-        for (int kc = 0; kc < MAX_KCHUNKS; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
-    }
-    // partial tiles -> LDS (over the staging buffers)
+    // partial tiles -> LDS: element (mb, j, e) of lane l at red_at(mb, e, l) + j, so that the thread
+    // that finishes e of every j reads four of them at once
+    auto red_at = [](int mb, int e, int l) { return ((mb * 4 + e) * 64 + l) * 4; };
     {
         float *red = lds.red(wave);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) red[((mb * 4 + j) * 4 + e) * 64 + lane] = acc[mb][j][e];
+            for (int e = 0; e < 4; ++e)
+                *reinterpret_cast<f32x4 *>(red + red_at(mb, e, lane)) =
+                    f32x4{acc[mb][0][e], acc[mb][1][e], acc[mb][2][e], acc[mb][3][e]};
     }
 
-    // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
-    if (fast) {
-        if (pf.t_mine) {
-            float v = 0.f;
+    constexpr int PU = 3;
+    // The common decode case gets a short, nearly branch-free way out (code that runs once per
+    // launch is paid for by the instruction fetch, so its length is its cost): a finishing block
+    // whose LoRA term, if any, was prefetched above and whose K has at most PU + 1 units.
+    const bool lean = PREFETCH && ku == 0 && (!lora || fast) && P.ksplit <= PU + 1;
+    if (lean) {
+        if constexpr (PREFETCH) {
+            const int m = m0 + elem_ml(0);
+            // this thread's entry of t: K-chunk partials of the shrink step, summed in fixed order
+            if (lora) {
+                float ts = 0.f;
+                if (pf.kch <= 4) {
+                    float tv[4];
 #pragma unroll
-            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? tv[kc] : 0.f;
-            lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
-        }
-    } else if (lora) {
-        for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
-            const int ml = idx / P.r16, jj = idx % P.r16;
-            const int ad = a.row_adapter[m0 + ml];
-            float v = 0.f;
-            if (ad >= 0 && ad < P.n_adapters)
-                for (int kc = 0; kc < P.kch; ++kc)
-                    v += load_shared(P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj);
-            lds.t_row(ml)[jj] = v * P.alpha;
-        }
-    }
-    MLORA_TRACE_POINT(trace_slot, 3);
-    __syncthreads();
-    MLORA_TRACE_POINT(trace_slot, 4);
-
+                    for (int kc = 0; kc < 4; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
 #pragma unroll
-    for (int qq = 0; qq < EPT; ++qq) {
-        const int i = wave * EPT + qq;
-        const int off = i * 64 + lane;
-        float v = lds.red(0)[off];
-#pragma unroll
-        for (int w = 1; w < WAVES; ++w) v += lds.red(w)[off];
-        const int ml = elem_ml(qq), col = elem_col(qq);
-        const int m = m0 + ml;
-        const int n = tile * TILE_N + col;
-        if (ku > 0) {
-            store_shared(P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col, v);
-            continue;
-        }
-        if (m < M && n < N) {
-#pragma unroll
-            for (int u = 0; u < PU; ++u)
-                if (u + 1 < P.ksplit) v += pv[qq][u];
-            for (int u = PU + 1; u < P.ksplit; ++u)
-                v += load_shared(P.partial + (((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col);
-            const int ad = elem_ad(qq);
-            if (ad >= 0) {
-                float l = 0.f;
-                if (fast) {
-                    if constexpr (PREFETCH) {
-                        l = dot8(pf.b[qq][0], lds.t_row(ml), l);
-                        if (P.rank > 8) l = dot8(pf.b[qq][1], lds.t_row(ml) + 8, l);
-                    }
+                    for (int kc = 0; kc < 4; ++kc) ts += kc < pf.kch ? tv[kc] : 0.f;
                 } else {
-                    const uint16_t *brow = P.lora_b + ((size_t)ad * N + n) * P.rank;
-                    for (int jj = 0; jj < P.rank; jj += 8)
-                        l = dot8(*reinterpret_cast<const uint4 *>(brow + jj), lds.t_row(ml) + jj, l);
+                    float tv[MAX_KCHUNKS];
+#pragma unroll
+                    for (int kc = 0; kc < MAX_KCHUNKS; ++kc)
+                        tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
+#pragma unroll
+                    for (int kc = 0; kc < MAX_KCHUNKS; ++kc) ts += kc < pf.kch ? tv[kc] : 0.f;
                 }
-                v += l;
+                if (pf.t_mine) lds.t_row(pf.t_ml)[pf.t_jj] = ts * P.alpha;
             }
-            if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
-            else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
+            float pv[EPT][PU];
+            if (P.ksplit > 1) {
+                const float *src = P.partial + ((size_t)tile * a.m_pad + min(m, M - 1)) * TILE_N + l16;
+                const size_t ustride = (size_t)tiles * a.m_pad * TILE_N;
+#pragma unroll
+                for (int qq = 0; qq < EPT; ++qq)
+#pragma unroll
+                    for (int u = 0; u < PU; ++u)
+                        pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride + 16 * qq);
+            }
+            MLORA_TRACE_POINT(trace_slot, 3);
+            __syncthreads();
+            MLORA_TRACE_POINT(trace_slot, 4);
+            f32x4 v = *reinterpret_cast<const f32x4 *>(lds.red(0) + red_at(0, wave, lane));
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w) v += *reinterpret_cast<const f32x4 *>(lds.red(w) + red_at(0, wave, lane));
+            if (P.ksplit > 1) {
+#pragma unroll
+                for (int qq = 0; qq < EPT; ++qq)
+#pragma unroll
+                    for (int u = 0; u < PU; ++u) v[qq] += u + 1 < P.ksplit ? pv[qq][u] : 0.f;
+            }
+            if (lora) {
+                float t[FAST_RANK];
+                const f32x4 *tr = reinterpret_cast<const f32x4 *>(lds.t_row(elem_ml(0)));
+#pragma unroll
+                for (int i = 0; i < FAST_RANK / 4; ++i) {
+                    const f32x4 tq = tr[i];
+                    t[4 * i] = tq[0]; t[4 * i + 1] = tq[1]; t[4 * i + 2] = tq[2]; t[4 * i + 3] = tq[3];
+                }
+                const bool mine = elem_ad(0) >= 0;
+                const bool two = P.rank > 8;
+#pragma unroll
+                for (int qq = 0; qq < EPT; ++qq) {
+                    float l = dot8(pf.b[qq][0], t, 0.f);
+                    if (two) l = dot8(pf.b[qq][1], t + 8, l);
+                    v[qq] += mine ? l : 0.f;
+                }
+            }
+            if (m < M) {
+                const int n0 = tile * TILE_N + l16;
+                if (a.y_fp32) {
+                    float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;
+#pragma unroll
+                    for (int qq = 0; qq < EPT; ++qq)
+                        if (n0 + 16 * qq < N) yp[16 * qq] = v[qq];
+                } else {
+                    uint16_t *yp = reinterpret_cast<uint16_t *>(P.y) + (size_t)m * N + n0;
+#pragma unroll
+                    for (int qq = 0; qq < EPT; ++qq)
+                        if (n0 + 16 * qq < N) yp[16 * qq] = float_to_bf16_bits(v[qq]);
+                }
+            }
+        }
+    } else {
+        // split-K partials of this thread's outputs: all requested at once (a thread with nothing to
+        // add re-reads a valid address), consumed after the reduction below
+        constexpr int PU = 3;
+        float pv[EPT][PU];
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq)
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int m = m0 + elem_ml(qq);
+                const bool ok = ku == 0 && u + 1 < P.ksplit && m < M;
+                const float *src = ok ? P.partial + (((size_t)u * tiles + tile) * a.m_pad + m) * TILE_N + elem_col(qq)
+                                      : reinterpret_cast<const float *>(P.codes);
+                pv[qq][u] = load_shared(src);
+            }
+        // one entry of t per thread (K-chunk partials of the shrink step, summed in fixed order)
+        float tv[MAX_KCHUNKS];
+        if (fast) {
+#pragma unroll
+            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
+        }
+
+        // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
+        if (fast) {
+            if (pf.t_mine) {
+                float v = 0.f;
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? tv[kc] : 0.f;
+                lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
+            }
+        } else if (lora) {
+            for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
+                const int ml = idx / P.r16, jj = idx % P.r16;
+                const int ad = a.row_adapter[m0 + ml];
+                float v = 0.f;
+                if (ad >= 0 && ad < P.n_adapters)
+                    for (int kc = 0; kc < P.kch; ++kc)
+                        v += load_shared(P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj);
+                lds.t_row(ml)[jj] = v * P.alpha;
+            }
+        }
+        MLORA_TRACE_POINT(trace_slot, 3);
+        __syncthreads();
+        MLORA_TRACE_POINT(trace_slot, 4);
+
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq) {
+            const int off = red_at(qq >> 2, wave, lane) + (qq & 3);
+            float v = lds.red(0)[off];
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w) v += lds.red(w)[off];
+            const int ml = elem_ml(qq), col = elem_col(qq);
+            const int m = m0 + ml;
+            const int n = tile * TILE_N + col;
+            if (ku > 0) {
+                store_shared(P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col, v);
+                continue;
+            }
+            if (m < M && n < N) {
+#pragma unroll
+                for (int u = 0; u < PU; ++u)
+                    if (u + 1 < P.ksplit) v += pv[qq][u];
+                for (int u = PU + 1; u < P.ksplit; ++u)
+                    v += load_shared(P.partial + (((size_t)(u - 1) * tiles + tile) * a.m_pad + m) * TILE_N + col);
+                const int ad = elem_ad(qq);
+                if (ad >= 0) {
+                    float l = 0.f;
+                    if (fast) {
+                        if constexpr (PREFETCH) {
+                            l = dot8(pf.b[qq][0], lds.t_row(ml), l);
+                            if (P.rank > 8) l = dot8(pf.b[qq][1], lds.t_row(ml) + 8, l);
+                        }
+                    } else {
+                        const uint16_t *brow = P.lora_b + ((size_t)ad * N + n) * P.rank;
+                        for (int jj = 0; jj < P.rank; jj += 8)
+                            l = dot8(*reinterpret_cast<const uint4 *>(brow + jj), lds.t_row(ml) + jj, l);
+                    }
+                    v += l;
+                }
+                if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
+                else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
+            }
         }
     }
-    if (ku > 0) signal_done(a.ctrl + P.part_ctr + tile * chunks + chunk);
+    if (ku > 0) signal_done(pctr, 1);
+    // Counters go back to zero for the next call: a tile's split-K counter once every wave has
+    // passed it (the barrier above), a copy of the shrink counter by the last block that used it.
+    if (tid == 0 && need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0 && need_s) {
+        const int users = P.n_finish_blocks / copies + (fin % copies < P.n_finish_blocks % copies ? 1 : 0);
+        if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
+            __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
@@ -555,7 +804,7 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
         tiles_before += nt;
     }
     if (seg < 0) {                                         // uniform over the block: nothing to do,
-        signal_done(a.ctrl + CTRL_SHRINK_DONE + pi);       // but the finishing blocks count it
+        signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));       // but the finishing blocks count it
         return;
     }
     const int adapter = g.seg_adapter[seg];
@@ -581,15 +830,16 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int s = 0;
     if (wave >= 4) s = my_cnt;                              // blocks may be wider than 4 waves
-    for (; s + 4 <= my_cnt; s += 4) {
-        uint4 xa[4], ab[4];
+    constexpr int SB = 8;                                   // k-steps requested at once
+    for (; s + SB <= my_cnt; s += SB) {
+        uint4 xa[SB], ab[SB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < SB; ++u) {
             xa[u] = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)(s + u) * KSTEP) : zero;
             ab[u] = j_ok ? *reinterpret_cast<const uint4 *>(ap + (size_t)(s + u) * KSTEP) : zero;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = mfma16(xa[u], ab[u], acc);
+        for (int u = 0; u < SB; ++u) acc = mfma16(xa[u], ab[u], acc);
     }
     for (; s < my_cnt; ++s) {
         const uint4 xa = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)s * KSTEP) : zero;
@@ -612,7 +862,7 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
             store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16, v);
         }
     }
-    signal_done(a.ctrl + CTRL_SHRINK_DONE + pi);
+    signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
@@ -623,8 +873,8 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
 // the rows of a chunk decides which instance runs): 4 waves per block, rounds of R k-steps
 // (two rounds = 2*R KiB of codes in flight per wave).
 template <int MB> struct Shape;
-template <> struct Shape<1> { static constexpr int WAVES = 4, R = 8, OCC = 2; };
-template <> struct Shape<2> { static constexpr int WAVES = 4, R = 4, OCC = 2; };
+template <> struct Shape<1> { static constexpr int WAVES = 4, R = 8; };
+template <> struct Shape<2> { static constexpr int WAVES = 4, R = 4; };
 
 template <int MB, int XR>
 using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>;
@@ -663,8 +913,11 @@ __device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH]
     return pi;
 }
 
+// blocks per compute unit the registers are budgeted for (LDS allows as many for these shapes)
+template <int MB, int XR> constexpr int occupancy_of() { return MB == 1 && XR == 8 ? 3 : 2; }
+
 template <int MB, int XR>
-__global__ __launch_bounds__(64 * Shape<MB>::WAVES, Shape<MB>::OCC) void layer_kernel(const LayerArgs a)
+__global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) void layer_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
     const int b = (int)blockIdx.x;

@@ -50,21 +50,20 @@ def proj(K=256, N=64, group=32, blob=0x1000, n_ad=2, rank=8, a=0x2000, b=0x3000,
 
 def test_workspace_bytes():
     cdll = lib.load_library()
-    # 256 B status header + 256 B of completion counters whenever blocks hand data to each other
-    ctl = 512
+    # 256 B status header + completion counters whenever blocks hand data to each other: 16
+    # projections x 16 copies of the shrink counters, each in a 128-byte line of its own
+    ctl = 256 + 16 * 16 * 128
     p = proj(K=2048, rank=16)
-    # K/512 = 4 chunks x M x rank16 x 4 bytes, rounded up to 256
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == ctl + 4 * 8 * 16 * 4
+    # K/1024 = 2 chunks (at most 16) x M x rank16 x 4 bytes, rounded up to 256
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == ctl + 2 * 8 * 16 * 4
     p = proj(K=256, rank=8)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == ctl + 256
     # K = 16384 = 8 units of 2048 inputs: 7 fp32 partial tiles [m_pad = 64][64] per tile of columns
     p = proj(K=16384, rank=64)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == ctl + 4 * 64 * 64 * 4 + 7 * 1 * 64 * 64 * 4
+    # (+ one counter line per (tile, row chunk) of a split-K projection: 1 tile x 2 chunks)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == ctl + 2 * 128 + 16 * 64 * 64 * 4 + 7 * 1 * 64 * 64 * 4
     p = proj(K=4096, N=200, n_ad=0, rank=0, a=None, b=None)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == ctl + 1 * 4 * 16 * 64 * 4
-    # one counter per (tile, row chunk) of a split-K projection after the 32 fixed ones
-    p = proj(K=4096, N=64 * 100, n_ad=0, rank=0, a=None, b=None)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == 256 + (32 + 100) * 4 // 256 * 256 + 256 + 100 * 16 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == ctl + 4 * 128 + 1 * 4 * 16 * 64 * 4
     p = proj(n_ad=0, rank=0, a=None, b=None)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 0
 
