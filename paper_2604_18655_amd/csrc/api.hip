@@ -245,7 +245,8 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                 d.kch = kch_of(p);
                 d.t_part = reinterpret_cast<float *>(ws);
                 ws += t_part_bytes(p, M);
-                d.n_shrink_blocks = max_row_tiles(M, p.n_adapters) * (d.r16 / 16) * d.kch;
+                // at most 16 rows: a shrink block per row; above: per 16-row tile of an adapter segment
+                d.n_shrink_blocks = (M <= 16 ? M : max_row_tiles(M, p.n_adapters)) * (d.r16 / 16) * d.kch;
                 shrink_blocks += d.n_shrink_blocks;
             } else {
                 d.n_adapters = 0;

@@ -319,10 +319,17 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[4], StreamRegs &ra, Str
         const bool last = ss + 2 >= n_ss;
         seen_s = __hip_atomic_load(last ? poll_s : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         seen_p = __hip_atomic_load(last ? poll_p : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef EXP_DEPTH1
+        stream_request(rb, wp0, sp0, ss + 1, n_ss, GS, lane);
+        stream_math<SPG>(acc, ra, xl + ss * 256, mask, bias);
+        stream_request(ra, wp0, sp0, ss + 2, n_ss, GS, lane);
+        if (ss + 1 < n_ss) stream_math<SPG>(acc, rb, xl + (ss + 1) * 256, mask, bias);
+#else
         stream_math<SPG>(acc, ra, xl + ss * 256, mask, bias);
         stream_request(ra, wp0, sp0, ss + 2, n_ss, GS, lane);
         if (ss + 1 < n_ss) stream_math<SPG>(acc, rb, xl + (ss + 1) * 256, mask, bias);
         stream_request(rb, wp0, sp0, ss + 3, n_ss, GS, lane);
+#endif
     }
 }
 
@@ -507,7 +514,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         StreamRegs sa, sb;
         // an idle wave requests (and ignores) the unit's first super-step
         stream_request(sa, wp, sp, 0, max(my_cnt, 1), 4 / P.spg, lane);
+#ifndef EXP_DEPTH1
         stream_request(sb, wp, sp, 1, my_cnt, 4 / P.spg, lane);
+#endif
         __builtin_amdgcn_sched_barrier(0);                     // (the requests stay ahead of the wait for x)
 #pragma unroll
         for (int i = 0; i < XR; ++i) *reinterpret_cast<u32x4 *>(buf + lane * 16 + i * L::XROW) = xr[i];
@@ -866,6 +875,93 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
+// Decode shapes (at most 16 rows): one block per (row, block of 16 ranks, K chunk) and no
+// grouping.  The row's adapter index is one scalar load away, so the block's requests go out
+// before the base blocks have filled the memory queues; rows that share an adapter read its A
+// once each, from the cache.  Row 0 of the MFMA's A operand carries x[m]; the other rows are 0.
+//
+// A[adapter] is read in runs of 512 contiguous bytes per rank row and turned into MFMA fragments
+// through a wave-private LDS buffer.  Reading the fragments directly (16 bytes from each of 16
+// rows per lane group) would address rows a power of two apart, which all lie in the same
+// memory channel: measured, those requests held up every other wave of their compute unit for
+// about 5 us.
+struct ShrinkRowLds {
+    static constexpr int SB = 8;                            // k-steps per batch
+    static constexpr int AROW = SB * 64 + 16;               // bytes of a rank row in a batch; +16: rows 4 banks apart
+    unsigned char a[4][16 * AROW];
+    unsigned char x[4][SB * 64];
+    float red[4][16];
+};
+
+__device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjArgs &P, int pi, int local,
+                                                 ShrinkRowLds &lds)
+{
+    using L = ShrinkRowLds;
+    constexpr int SB = L::SB;
+    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    MLORA_TRACE_POINT(trace_slot, 0);
+    const int jblocks = P.r16 / 16;
+    const int kc = local % P.kch;
+    const int jb = (local / P.kch) % jblocks;
+    const int m = local / (P.kch * jblocks);               // < M: the grid has M such rows of blocks
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int half = lane >> 5, l32 = lane & 31;            // loads: two rank rows per instruction
+
+    // k-steps of this block, then of this wave (balanced splits)
+    const int nks = P.K / KSTEP;
+    const int q = nks / P.kch, r = nks % P.kch;
+    const int blk_beg = kc * q + min(kc, r), blk_cnt = q + (kc < r ? 1 : 0);
+    const int wq_ = blk_cnt / 4, wr = blk_cnt % 4;
+    const int my_beg = blk_beg + wave * wq_ + min(wave, wr);
+    const int my_cnt = wq_ + (wave < wr ? 1 : 0);
+
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const int adapter = a.row_adapter[m];
+    const bool valid = adapter >= 0 && adapter < P.n_adapters;      // uniform
+    const uint16_t *xrow = P.x + (size_t)m * P.K + (size_t)my_beg * KSTEP + l32 * 8;
+    const uint16_t *arow = P.lora_a + (size_t)(valid ? adapter : 0) * P.rank * P.K + (size_t)my_beg * KSTEP + l32 * 8;
+    unsigned char *la = lds.a[wave], *lx = lds.x[wave];
+    MLORA_TRACE_POINT(trace_slot, 1);
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < my_cnt && valid; s0 += SB) {
+        const int cnt = min(SB, my_cnt - s0);               // k-steps of this batch
+        const bool k_ok = (l32 >> 2) < cnt;                 // this lane's 8 inputs lie in k-step l32/4
+        const u32x4 xv = (half == 0 && k_ok) ? *reinterpret_cast<const u32x4 *>(xrow + (size_t)s0 * KSTEP) : zero;
+        u32x4 av[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = jb * 16 + 2 * i + half;
+            av[i] = (k_ok && j < P.rank) ? *reinterpret_cast<const u32x4 *>(arow + (size_t)j * P.K + (size_t)s0 * KSTEP)
+                                         : zero;
+        }
+        if (half == 0) *reinterpret_cast<u32x4 *>(lx + l32 * 16) = xv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(la + (2 * i + half) * L::AROW + l32 * 16) = av[i];
+        // (wave-private buffer: the wave's own LDS accesses are ordered, no barrier)
+#pragma unroll
+        for (int s = 0; s < SB; ++s) {
+            const uint4 ab = *reinterpret_cast<const uint4 *>(la + l16 * L::AROW + s * 64 + 16 * lq);
+            uint4 xa = *reinterpret_cast<const uint4 *>(lx + s * 64 + 16 * lq);
+            if (l16 != 0) xa = make_uint4(0, 0, 0, 0);
+            acc = mfma16(xa, ab, acc);
+        }
+    }
+    if (valid) {
+        // row 0 of the result: element 0 of lanes 0..15
+        if (lq == 0) lds.red[wave][l16] = acc[0];
+        __syncthreads();
+        if (tid < 16) {
+            const float v = ((lds.red[0][tid] + lds.red[1][tid]) + lds.red[2][tid]) + lds.red[3][tid];
+            store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + tid, v);
+        }
+    }
+    // (a base-only row has nothing to write, but the finishing blocks count its blocks all the same)
+    signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));
+    MLORA_TRACE_POINT(trace_slot, 5);
+}
+
 // ------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------
@@ -881,7 +977,8 @@ using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>;
 template <int MB, int XR>
 constexpr int pre_lds_bytes()
 {
-    return BaseLdsOf<MB, XR>::BYTES > (int)sizeof(ShrinkLds) ? BaseLdsOf<MB, XR>::BYTES : (int)sizeof(ShrinkLds);
+    constexpr int shrink = sizeof(ShrinkLds) > sizeof(ShrinkRowLds) ? (int)sizeof(ShrinkLds) : (int)sizeof(ShrinkRowLds);
+    return BaseLdsOf<MB, XR>::BYTES > shrink ? BaseLdsOf<MB, XR>::BYTES : shrink;
 }
 
 // Fetch every field of a projection's argument block at once.  Kernel arguments sit behind a
@@ -925,7 +1022,8 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     if (b < a.shrink_blocks) {
         if (blockIdx.y != 0) return;
         const int pi = find_proj(a.shrink_begin, b, first);
-        shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        if (a.M <= 16) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
+        else           shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     const BaseLdsOf<MB, XR> lds{smem};
