@@ -319,17 +319,10 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[4], StreamRegs &ra, Str
         const bool last = ss + 2 >= n_ss;
         seen_s = __hip_atomic_load(last ? poll_s : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         seen_p = __hip_atomic_load(last ? poll_p : dummy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#ifdef EXP_DEPTH1
-        stream_request(rb, wp0, sp0, ss + 1, n_ss, GS, lane);
-        stream_math<SPG>(acc, ra, xl + ss * 256, mask, bias);
-        stream_request(ra, wp0, sp0, ss + 2, n_ss, GS, lane);
-        if (ss + 1 < n_ss) stream_math<SPG>(acc, rb, xl + (ss + 1) * 256, mask, bias);
-#else
         stream_math<SPG>(acc, ra, xl + ss * 256, mask, bias);
         stream_request(ra, wp0, sp0, ss + 2, n_ss, GS, lane);
         if (ss + 1 < n_ss) stream_math<SPG>(acc, rb, xl + (ss + 1) * 256, mask, bias);
         stream_request(rb, wp0, sp0, ss + 3, n_ss, GS, lane);
-#endif
     }
 }
 
@@ -514,9 +507,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         StreamRegs sa, sb;
         // an idle wave requests (and ignores) the unit's first super-step
         stream_request(sa, wp, sp, 0, max(my_cnt, 1), 4 / P.spg, lane);
-#ifndef EXP_DEPTH1
         stream_request(sb, wp, sp, 1, my_cnt, 4 / P.spg, lane);
-#endif
         __builtin_amdgcn_sched_barrier(0);                     // (the requests stay ahead of the wait for x)
 #pragma unroll
         for (int i = 0; i < XR; ++i) *reinterpret_cast<u32x4 *>(buf + lane * 16 + i * L::XROW) = xr[i];
