@@ -345,11 +345,14 @@ struct EpiPrefetch {
         // the top of the kernel and then spills their results across the whole K loop
         asm volatile("" : "+v"(bad));
         const int second = brank > 8 ? 8 : 0;
+        // (global, not generic, loads: a generic load also counts as an LDS access, and every
+        // later wait for LDS would wait for these as well)
+        using G = const __attribute__((address_space(1))) u32x4;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
             const uint16_t *row = bad + (unsigned)(min(n0 + 16 * q, nlast) * brank);
-            b[q][0] = *reinterpret_cast<const uint4 *>(row);
-            b[q][1] = *reinterpret_cast<const uint4 *>(row + second);
+            b[q][0] = __builtin_bit_cast(uint4, *(G *)(row));
+            b[q][1] = __builtin_bit_cast(uint4, *(G *)(row + second));
         }
     }
 };
