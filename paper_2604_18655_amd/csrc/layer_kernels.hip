@@ -776,13 +776,24 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 // ------------------------------------------------------------------------------------------
 // LoRA shrink
 // ------------------------------------------------------------------------------------------
+// Rows of x and rank rows of A are both K elements apart, a power of two as a rule: a request
+// that takes 16 bytes from each of 16 such rows (an MFMA fragment read directly) lands in one
+// memory channel and holds up every other wave of its compute unit.  So both are read in
+// contiguous runs (4 rows x 256 bytes per instruction) and turned into fragments through a
+// wave-private LDS buffer, four k-steps at a time.
 struct ShrinkLds {
+    static constexpr int SB = 4;                            // k-steps per batch
+    static constexpr int ROW = SB * 64 + 16;                // bytes of a staged row; +16: rows 4 banks apart
     GroupLds g;
     float red[4][256];
+    unsigned char a[4][16 * ROW];
+    unsigned char x[4][16 * ROW];
 };
 
 __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int pi, int local, ShrinkLds &lds)
 {
+    using L = ShrinkLds;
+    constexpr int SB = L::SB;
     GroupLds &g = lds.g;
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
     MLORA_TRACE_POINT(trace_slot, 0);
@@ -821,40 +832,53 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     const int q = nks / P.kch, r = nks % P.kch;
     const int blk_beg = kc * q + min(kc, r), blk_cnt = q + (kc < r ? 1 : 0);
     const int wq_ = blk_cnt / 4, wr = blk_cnt % 4;
-    const int my_beg = blk_beg + (wave & 3) * wq_ + min(wave & 3, wr), my_cnt = wq_ + ((wave & 3) < wr ? 1 : 0);
+    const int my_beg = blk_beg + wave * wq_ + min(wave, wr), my_cnt = wq_ + (wave < wr ? 1 : 0);
 
-    const int row = (l16 < rows_here) ? (int)g.perm[first + l16] : -1;
-    const int j = jb * 16 + l16;
-    const bool j_ok = j < P.rank;
-    const uint16_t *xp = P.x + (size_t)(row < 0 ? 0 : row) * P.K + 8 * lq + (size_t)my_beg * KSTEP;
-    const uint16_t *ap = P.lora_a + ((size_t)adapter * P.rank + (j_ok ? j : 0)) * P.K + 8 * lq +
-                         (size_t)my_beg * KSTEP;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    if (wave >= 4) s = my_cnt;                              // blocks may be wider than 4 waves
-    constexpr int SB = 8;                                   // k-steps requested at once
-    for (; s + SB <= my_cnt; s += SB) {
-        uint4 xa[SB], ab[SB];
+    // loads: instruction i covers staged rows 4*i + lane/16, 16 bytes per lane (lane%16 of 16)
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const uint16_t *xsrc[4], *asrc[4];
+    bool x_ok[4], a_ok[4];
 #pragma unroll
-        for (int u = 0; u < SB; ++u) {
-            xa[u] = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)(s + u) * KSTEP) : zero;
-            ab[u] = j_ok ? *reinterpret_cast<const uint4 *>(ap + (size_t)(s + u) * KSTEP) : zero;
+    for (int i = 0; i < 4; ++i) {
+        const int rr = 4 * i + lq;                          // staged row: tile row of x, rank row of A
+        x_ok[i] = rr < rows_here;
+        const int row = x_ok[i] ? (int)g.perm[first + rr] : 0;
+        xsrc[i] = P.x + (size_t)row * P.K + (size_t)my_beg * KSTEP + l16 * 8;
+        const int j = jb * 16 + rr;
+        a_ok[i] = j < P.rank;
+        asrc[i] = P.lora_a + ((size_t)adapter * P.rank + (a_ok[i] ? j : 0)) * P.K + (size_t)my_beg * KSTEP + l16 * 8;
+    }
+    unsigned char *la = lds.a[wave], *lx = lds.x[wave];
+    u32x4 xv[4], av[4];
+    auto request = [&](int s0) {
+        const bool k_ok = (l16 >> 2) < my_cnt - s0;         // this lane's 8 inputs lie in k-step s0 + l16/4
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            xv[i] = (x_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)s0 * KSTEP) : zero;
+            av[i] = (a_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(asrc[i] + (size_t)s0 * KSTEP) : zero;
         }
+    };
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (my_cnt > 0) request(0);
+    for (int s0 = 0; s0 < my_cnt; s0 += SB) {
 #pragma unroll
-        for (int u = 0; u < SB; ++u) acc = mfma16(xa[u], ab[u], acc);
-    }
-    for (; s < my_cnt; ++s) {
-        const uint4 xa = row >= 0 ? *reinterpret_cast<const uint4 *>(xp + (size_t)s * KSTEP) : zero;
-        const uint4 ab = j_ok ? *reinterpret_cast<const uint4 *>(ap + (size_t)s * KSTEP) : zero;
-        acc = mfma16(xa, ab, acc);
-    }
-    if (wave < 4) {
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<u32x4 *>(lx + (4 * i + lq) * L::ROW + l16 * 16) = xv[i];
+            *reinterpret_cast<u32x4 *>(la + (4 * i + lq) * L::ROW + l16 * 16) = av[i];
+        }
+        if (s0 + SB < my_cnt) request(s0 + SB);             // next batch on its way during the math
+        // (wave-private buffers: the wave's own LDS accesses are ordered, no barrier)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) lds.red[wave][e * 64 + lane] = acc[e];
+        for (int s = 0; s < SB; ++s) {
+            const uint4 xa = *reinterpret_cast<const uint4 *>(lx + l16 * L::ROW + s * 64 + 16 * lq);
+            const uint4 ab = *reinterpret_cast<const uint4 *>(la + l16 * L::ROW + s * 64 + 16 * lq);
+            acc = mfma16(xa, ab, acc);
+        }
     }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lds.red[wave][e * 64 + lane] = acc[e];
     __syncthreads();
-    if (wave < 4) {
+    {
         // thread (e, lane) owns tile row 4*(lane/16) + e and rank column lane%16
         const int e = wave;
         const int i = 4 * lq + e;
@@ -971,7 +995,7 @@ using BaseLdsOf = BaseLds<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>;
 template <int MB, int XR>
 constexpr int pre_lds_bytes()
 {
-    constexpr int shrink = sizeof(ShrinkLds) > sizeof(ShrinkRowLds) ? (int)sizeof(ShrinkLds) : (int)sizeof(ShrinkRowLds);
+    constexpr int shrink = MB == 1 ? (int)sizeof(ShrinkRowLds) : (int)sizeof(ShrinkLds);   // (MB == 1: M <= 16)
     return BaseLdsOf<MB, XR>::BYTES > shrink ? BaseLdsOf<MB, XR>::BYTES : shrink;
 }
 
@@ -1016,8 +1040,9 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     if (b < a.shrink_blocks) {
         if (blockIdx.y != 0) return;
         const int pi = find_proj(a.shrink_begin, b, first);
-        if (a.M <= 16) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
-        else           shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        // (the instances with one block of 16 rows are the ones launched for M <= 16)
+        if constexpr (MB == 1) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
+        else                   shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     const BaseLdsOf<MB, XR> lds{smem};
