@@ -44,15 +44,39 @@ size_t t_part_bytes(const mlora_w4_proj &p, int M)
     return round_up((size_t)kch_of(p) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
 }
 
-int ksplit_of(const mlora_w4_proj &p)
+int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
+
+// K units per column tile.  Decode kernels: units of at most 2048 inputs (what a block stages of
+// x).  Wide kernel (64 rows and more): any unit length works, and a launch with few blocks is cut
+// further, down to 4 super-steps per unit, until it has about 256 of them; `launch_blocks` =
+// base blocks of the whole launch before that extra cut.
+int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
 {
     const int nss = p.K / SUPER_K;
-    return (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
+    int ks = (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
+    if (M >= WIDE_MIN_ROWS && launch_blocks > 0) {
+        const int factor = (256 + launch_blocks - 1) / launch_blocks;
+        const int most = nss / 4 > 1 ? nss / 4 : 1;
+        const int cut = ks * factor < most ? ks * factor : most;
+        if (cut > ks) ks = cut;
+    }
+    return ks;
 }
-int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
-size_t partial_bytes(const mlora_w4_proj &p, int M)
+// base blocks of a launch over `count` projections with the default K units
+int launch_blocks_of(const mlora_w4_proj *projs, int count, int M)
 {
-    return (size_t)(ksplit_of(p) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
+    int n = 0;
+    const int chunks = m_pad_of(M) / rows_per_chunk(M);
+    for (int i = 0; i < count; ++i) {
+        const int nss = projs[i].K / SUPER_K;
+        n += (tiles_n(projs[i].N) + tiles_per_block(M) - 1) / tiles_per_block(M) * chunks *
+             ((nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS);
+    }
+    return n;
+}
+size_t partial_bytes(const mlora_w4_proj &p, int M, int launch_blocks)
+{
+    return (size_t)(ksplit_of(p, M, launch_blocks) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
 }
 
 // upper bound of the number of 16-row tiles the adapter segments of M rows can form
@@ -121,6 +145,17 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                              (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }
 
+// Projections of one launch: up to 16, and for the wide kernel (64 rows and more, compiled per
+// group size) only as long as the group size stays the same.
+static int launch_run(const mlora_w4_proj *projs, int n_left, int M)
+{
+    int count = 1;
+    while (count < n_left && count < MAX_PROJ_PER_LAUNCH &&
+           (M < WIDE_MIN_ROWS || projs[count].group == projs[0].group))
+        ++count;
+    return count;
+}
+
 // Workspace layout: [status word, 256 B][counters of launch 0][counters of launch 1]...[data].
 // Counters exist only if something is shared between blocks (LoRA or split-K).
 static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M, bool lora)
@@ -128,7 +163,7 @@ static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M,
     size_t n = 0;                              // counter lines of the split-K tiles
     bool any = false;
     for (int i = 0; i < count; ++i) {
-        if (ksplit_of(projs[i]) > 1) {
+        if (ksplit_of(projs[i], M, launch_blocks_of(projs, count, M)) > 1) {
             n += (size_t)tiles_n(projs[i].N) * (size_t)(m_pad_of(M) / rows_per_chunk(M));
             any = true;
         }
@@ -140,8 +175,8 @@ static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M,
 static size_t ctrl_bytes_total(const mlora_w4_proj *projs, int n_proj, int M, bool lora)
 {
     size_t total = 0;
-    for (int first = 0; first < n_proj; first += MAX_PROJ_PER_LAUNCH) {
-        const int count = (n_proj - first < MAX_PROJ_PER_LAUNCH) ? n_proj - first : MAX_PROJ_PER_LAUNCH;
+    for (int first = 0, count = 0; first < n_proj; first += count) {
+        count = launch_run(projs + first, n_proj - first, M);
         total += ctrl_bytes_of_launch(projs + first, count, M, lora);
     }
     return total ? total + WS_HEADER_BYTES : 0;
@@ -151,7 +186,11 @@ size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int3
 {
     if (!projs || n_proj <= 0 || M <= 0) return 0;
     size_t total = ctrl_bytes_total(projs, n_proj, M, true);
-    for (int i = 0; i < n_proj; ++i) total += t_part_bytes(projs[i], M) + partial_bytes(projs[i], M);
+    for (int first = 0, count = 0; first < n_proj; first += count) {
+        count = launch_run(projs + first, n_proj - first, M);
+        const int lb = launch_blocks_of(projs + first, count, M);
+        for (int i = first; i < first + count; ++i) total += t_part_bytes(projs[i], M) + partial_bytes(projs[i], M, lb);
+    }
     return total;
 }
 
@@ -194,8 +233,8 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
     char *ctrl = reinterpret_cast<char *>(workspace) + WS_HEADER_BYTES;
     char *ws = reinterpret_cast<char *>(workspace) + ctrl_bytes_total(projs, n_proj, M, true);
     const int chunks = m_pad_of(M) / rows_per_chunk(M);
-    for (int first = 0; first < n_proj; first += MAX_PROJ_PER_LAUNCH) {
-        const int count = (n_proj - first < MAX_PROJ_PER_LAUNCH) ? n_proj - first : MAX_PROJ_PER_LAUNCH;
+    for (int first = 0, count = 0; first < n_proj; first += count) {
+        count = launch_run(projs + first, n_proj - first, M);
         LayerArgs a;
         memset(&a, 0, sizeof a);
         a.row_adapter = any_lora ? row_adapter : nullptr;
@@ -212,6 +251,7 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             a.ctrl = reinterpret_cast<unsigned *>(ctrl);
             ctrl += ctrl_bytes_of_launch(projs + first, count, M, true);
         }
+        const int lb = launch_blocks_of(projs + first, count, M);
         int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0, part_ctr = CTRL_PART;
         for (int i = 0; i < count; ++i) {
             const mlora_w4_proj &p = projs[first + i];
@@ -225,14 +265,16 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             d.N = p.N;
             d.spg = p.group / KSTEP;
             d.alpha = p.alpha;
-            d.ksplit = ksplit_of(p);
+            d.ksplit = ksplit_of(p, M, lb);
             d.n_finish_blocks = tiles_n(p.N) * chunks;
+            // base blocks: one per column tile, or per four of them for 64 rows and more
+            const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
             a.main_begin[i] = main_blocks;
-            main_blocks += tiles_n(p.N);
+            main_blocks += col_blocks;
             a.pre_begin[i] = pre_blocks;
-            pre_blocks += tiles_n(p.N) * (d.ksplit - 1);
+            pre_blocks += col_blocks * (d.ksplit - 1);
             d.partial = reinterpret_cast<float *>(ws);
-            ws += partial_bytes(p, M);
+            ws += partial_bytes(p, M, lb);
             d.part_ctr = part_ctr;
             if (d.ksplit > 1) part_ctr += tiles_n(p.N) * chunks * CTR_STRIDE;
             a.shrink_begin[i] = shrink_blocks;

@@ -162,6 +162,10 @@ hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s);
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
-__host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : 32; }
+constexpr int WIDE_MIN_ROWS = 64;      // calls with at least this many rows take the wide kernel
+constexpr int WIDE_TILES_PER_BLOCK = 4;
+__host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : M < WIDE_MIN_ROWS ? 32 : 64; }
+// column tiles a base block covers
+__host__ __device__ inline int tiles_per_block(int M) { return M < WIDE_MIN_ROWS ? 1 : WIDE_TILES_PER_BLOCK; }
 
 }  // namespace mlora

@@ -1062,6 +1062,489 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Wide shapes (64 rows or more per call): the product is a dense contraction and the matrix
+// units are what bounds it.  A block covers 64 rows x 256 columns: its four waves share the rows
+// of x (staged in LDS, one super-step of 128 inputs at a time, double-buffered) and each wave
+// owns one 64-column tile, whose packed codes it streams into registers two super-steps ahead
+// and unpacks once for all 64 rows (4 A fragments x 4 B fragments = 16 MFMAs per k-step, plus
+// 4 for the offset term).  No K split inside the block; long K is cut into units as for the
+// decode shapes, and a launch with few blocks is cut further by the host.
+//
+// Scales without a second set of accumulators: the accumulator is kept in units of the current
+// group's scale, acc <- acc * (s_prev / s_cur) + (offset term), and the MFMAs of the group add
+// their raw code products to it; the last scale is applied at the end.  A zero scale (padding
+// columns; legal in a hand-made blob) keeps the previous unit and its codes are replaced by
+// code 0, so it contributes exactly nothing.
+//
+// LoRA term on the matrix units too: t[m] (fp32, from the shrink blocks) is split into two bf16
+// halves (hi + lo keeps 16 bits of mantissa), and for every adapter that occurs in the chunk of
+// 64 rows its rows of B for the tile are fetched once (four adapters per round trip) and one
+// MFMA pair per 16 columns and 32 ranks adds B[a] . t for every block of 16 rows that holds such
+// a row, the rows of other adapters masked to zero.
+// ------------------------------------------------------------------------------------------
+constexpr int WIDE_ROWS = 64, WIDE_TILES = 4;
+
+struct WideLds {
+    static constexpr int XROW = 4 * 64 + 16;               // bytes of a row of x per super-step; +16: rows 4 banks apart
+    static constexpr int X_STAGE = WIDE_ROWS * XROW;
+    static constexpr int T_STRIDE = MLORA_MAX_RANK + 4;    // floats per row of t
+    static constexpr int T_BYTES = WIDE_ROWS * T_STRIDE * 4;
+    static constexpr int BUF_BYTES = 2 * X_STAGE > T_BYTES ? 2 * X_STAGE : T_BYTES;
+    alignas(16) unsigned char buf[BUF_BYTES];              // x stages; after the K loop: t
+    alignas(16) float stage[WIDE_TILES][16 * (TILE_N + 4)]; // per wave: 16 rows of outputs on their way out
+    int ad[WIDE_ROWS];                                     // adapter of each row of the chunk (-1: none)
+};
+
+struct WideRegs {
+    u32x4 w[4];
+    uint2 sc[4];
+};
+
+// Request super-step ss of the unit (n_ss super-steps; past the end: one 16-byte read of the first chunk).
+__device__ __forceinline__ void wide_request(WideRegs &r, const u32x4 *wp0, const uint2 *sp0, int ss, int n_ss,
+                                             int gs, int lane)
+{
+    const bool in = ss < n_ss;
+    const u32x4 *wn = wp0 + (in ? (size_t)ss * 256 + lane : 0);
+    const uint2 *sn = sp0 + (in ? (size_t)ss * gs * 16 + (lane & 15) : 0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) r.w[u] = wn[in ? u * 64 : 0];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) r.sc[g] = sn[in ? min(g, gs - 1) * 16 : 0];
+}
+
+// One super-step of the 64 x 64 tile; xs = this lane's fragment of row block 0, k-step 0 in the
+// LDS stage (row lane%16, 16 bytes number lane/16 of the k-step; indexed in units of 16 bytes:
+// a row block is XROW of them further, a k-step 4); prev = scale unit of acc per column block.
+template <int SPG>
+__device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], const WideRegs &r,
+                                          const uint4 *xs, uint32_t mask, uint32_t bias)
+{
+    constexpr int GS = 4 / SPG;
+    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
+    constexpr uint32_t CODE0 = 0x88888888u;                // eight codes 0 (offset binary 8), before placing the fields
+#pragma unroll
+    for (int g = 0; g < GS; ++g) {
+        const uint2 sv = r.sc[g];
+        float ratio[4];
+        bool dead[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
+                           : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
+            dead[j] = sj == 0.f;
+            const float unit = dead[j] ? (prev[j] == 0.f ? 1.f : prev[j]) : sj;
+            // (one rounding per change of unit: 2^-23 relative, a few dozen times over K)
+            ratio[j] = prev[j] * __builtin_amdgcn_rcpf(unit);
+
+            if (unit == prev[j]) ratio[j] = 1.f;
+            prev[j] = unit;
+        }
+
+        // offset term of the group: -24 * sum of x over its inputs, per row
+        f32x4 corr[4];
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < SPG; ++t) {
+                const uint4 xa = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+                corr[mb] = mfma16(xa, neg24, corr[mb]);
+            }
+        }
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(acc[mb][j][e], ratio[j], corr[mb][e]);
+#pragma unroll
+        for (int t = 0; t < SPG; ++t) {
+            uint4 xa[4];
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+                xa[mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+            const u32x4 wv = r.w[g * SPG + t];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
+
+                // a dead column's codes become code 0 (the field layout is the same in every dword)
+                wj = dead[j] ? rotl32(CODE0, 3) : wj;
+                const uint4 wb = expand_codes(wj, mask, bias);
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) acc[mb][j] = mfma16(xa[mb], wb, acc[mb][j]);
+            }
+        }
+    }
+}
+
+// eight fp32 -> the bf16 A-operand fragments of their high and low halves
+__device__ __forceinline__ void split_bf16(const float (&v)[8], uint4 &hi, uint4 &lo)
+{
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        h[i] = __float_as_uint(v[i]) & 0xFFFF0000u;
+        l[i] = __float_as_uint(v[i] - __uint_as_float(h[i])) & 0xFFFF0000u;
+    }
+    hi = make_uint4((h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]);
+    lo = make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]);
+}
+
+// group = index of the block's four tiles among the projection's; ku as in base_unit.  SPG =
+// k-steps per scale group, the same for every projection of the launch.
+template <int SPG>
+__device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P, int pi, int group, int ku,
+                                          int m0, WideLds &lds)
+{
+    using L = WideLds;
+    const int K = P.K, N = P.N, M = a.M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int tiles = tiles_n(N);
+    const int tile_raw = group * WIDE_TILES + wave;
+    const bool tile_ok = tile_raw < tiles;                 // (uniform per wave; a spare wave computes and drops tile 0)
+    const int tile = tile_ok ? tile_raw : 0;
+
+    const int nss = K / SUPER_K;
+    const int uq = nss / P.ksplit, ur = nss % P.ksplit;
+    const int unit_beg = ku * uq + min(ku, ur), unit_cnt = uq + (ku < ur ? 1 : 0);
+    const int ksteps = K / KSTEP;
+    constexpr int gs = 4 / SPG;
+    const u32x4 *wp = reinterpret_cast<const u32x4 *>(P.codes + (size_t)tile * ksteps * 64) + (size_t)unit_beg * 256;
+    const uint2 *sp = P.scales + ((size_t)tile * (ksteps / SPG) + (size_t)unit_beg * gs) * 16;
+
+    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + wave + (int)blockIdx.y * (int)gridDim.x * 4;
+    MLORA_TRACE_POINT(trace_slot, 0);
+    const bool lora = ku == 0 && a.row_adapter != nullptr && P.n_adapters > 0;
+    const int rows_here = min(WIDE_ROWS, M - m0);
+    const int chunk = m0 / WIDE_ROWS, chunks = a.m_pad / WIDE_ROWS;
+    const int fin = tile * chunks + chunk;
+    const int copies = min(CTR_REPL, P.n_finish_blocks);
+    unsigned *const sctr = a.ctrl + shrink_ctr(pi, fin % copies);
+    unsigned *const pctr = a.ctrl + P.part_ctr + fin * CTR_STRIDE;
+    const bool need_s = lora, need_p = ku == 0 && P.ksplit > 1;
+
+    const uint32_t mask = a.code_mask;
+    uint32_t bias = a.code_bias;
+    asm volatile("" : "+v"(bias));
+
+    // rows of x: thread t moves, per stage, 16 bytes of rows t/16 + 16*i (i = 0..3)
+    const uint16_t *xsrc[4];
+    int xdst[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 16 * i + (tid >> 4);
+        xsrc[i] = P.x + (size_t)(m0 + min(row, rows_here - 1)) * K + (size_t)unit_beg * SUPER_K + (tid & 15) * 8;
+        xdst[i] = row * L::XROW + (tid & 15) * 16;
+    }
+    const uint4 *xfrag = reinterpret_cast<const uint4 *>(lds.buf) + l16 * (L::XROW / 16) + lq;
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float prev[4] = {0.f, 0.f, 0.f, 0.f};
+
+    WideRegs ra, rb;
+    u32x4 xr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+    wide_request(ra, wp, sp, 0, unit_cnt, gs, lane);
+    wide_request(rb, wp, sp, 1, unit_cnt, gs, lane);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + xdst[i]) = xr[i];
+
+    auto math = [&](const WideRegs &r, int stage) {
+        wide_math<SPG>(acc, prev, r, xfrag + stage * (L::X_STAGE / 16), mask, bias);
+    };
+    MLORA_TRACE_POINT(trace_slot, 7);
+#pragma nounroll
+    for (int ss = 0; ss < unit_cnt; ss += 2) {
+
+        // stage ss: set A, x buffer 0
+        __syncthreads();                                   // its rows of x are in place; buffer 1 is free
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)min(ss + 1, unit_cnt - 1) * SUPER_K);
+        math(ra, 0);
+        wide_request(ra, wp, sp, ss + 2, unit_cnt, gs, lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + L::X_STAGE + xdst[i]) = xr[i];
+
+        // stage ss + 1: set B, x buffer 1
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)min(ss + 2, unit_cnt - 1) * SUPER_K);
+        if (ss + 1 < unit_cnt) math(rb, 1);
+        wide_request(rb, wp, sp, ss + 3, unit_cnt, gs, lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + xdst[i]) = xr[i];
+    }
+    MLORA_TRACE_POINT(trace_slot, 2);
+
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[mb][j][e] *= prev[j];
+
+    // element (mb, j, e) of this lane: row 16*mb + 4*lq + e of the chunk, column 16*j + l16 of the tile
+    if (ku > 0) {
+        if (tile_ok) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) store_shared(dst + 16 * j, acc[mb][j][e]);
+                }
+            __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's stores have completed
+            if (lane == 0) atomicAdd(pctr, 1u);
+        }
+        return;
+    }
+
+    // what this wave's tile needs from other blocks
+    if (tile_ok) {
+        bool ok = true;
+        if (need_s) ok = wait_count(sctr, (unsigned)P.n_shrink_blocks);
+        if (need_p) ok = wait_count(pctr, (unsigned)(P.ksplit - 1)) && ok;
+        if (!ok && lane == 0) atomicOr(a.status, 1u);
+        if (need_p) {
+            for (int u = 0; u + 1 < P.ksplit; ++u)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[mb][j][e] += load_shared(src + 16 * j);
+                    }
+        }
+    }
+    MLORA_TRACE_POINT(trace_slot, 8);
+    if (lora) {                                            // (uniform over the block)
+        // a spare wave has not looked at the shrink counter: it must, before it reads t
+
+        if (!tile_ok && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
+        __syncthreads();                                   // every wave is done with the x buffers
+        float *tl = reinterpret_cast<float *>(lds.buf);
+        const int r32 = (P.r16 + 31) / 32 * 32;            // ranks as the MFMAs see them (zero-filled)
+        // t = alpha * sum over the K chunks of the shrink partials, in fixed order; requested in
+        // batches of 4 entries x 4 chunks so that the round trips overlap
+
+        for (int i0 = 0; i0 < WIDE_ROWS * r32; i0 += 4 * 256) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int kc0 = 0; kc0 < P.kch; kc0 += 4) {
+                float pv[4][4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = i0 + q * 256 + tid;
+                    const int ml = idx / r32, jj = idx % r32;
+                    const bool live = ml < rows_here && jj < P.r16;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int kc = min(kc0 + c, P.kch - 1);
+                        const float *src = live ? P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj : P.t_part;
+                        pv[q][c] = load_shared(src);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) v[q] += kc0 + c < P.kch ? pv[q][c] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int idx = i0 + q * 256 + tid;
+                const int ml = idx / r32, jj = idx % r32;
+                if (ml < WIDE_ROWS) tl[ml * L::T_STRIDE + jj] = (ml < rows_here && jj < P.r16) ? v[q] * P.alpha : 0.f;
+            }
+        }
+        if (tid < WIDE_ROWS) {
+            const int v = tid < rows_here ? a.row_adapter[m0 + tid] : -1;
+            lds.ad[tid] = (v >= 0 && v < P.n_adapters) ? v : -1;
+        }
+        __syncthreads();
+        MLORA_TRACE_POINT(trace_slot, 3);
+        if (tile_ok) {
+
+            // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
+            // tile's 64 columns are fetched once and used by every block of 16 rows that holds
+            // such a row.  Four adapters are fetched per round trip.
+            const int n_lane = tile * TILE_N + l16;
+            const int ad_row = lds.ad[lane];                // lane l looks after row l of the chunk
+            const unsigned long long all = __ballot(ad_row >= 0);
+            auto b_request = [&](u32x4 (&bf)[4], int cur, int kk) {
+                const bool k_ok = 32 * kk + 8 * lq < P.rank;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = min(n_lane + 16 * j, N - 1);
+                    bf[j] = *reinterpret_cast<const u32x4 *>(P.lora_b + ((size_t)cur * N + n) * P.rank +
+                                                             (k_ok ? 32 * kk + 8 * lq : 0));
+                }
+            };
+            for (int kk = 0; kk < r32 / 32; ++kk) {
+                const bool k_ok = 32 * kk + 8 * lq < P.rank;
+                unsigned long long remaining = all;
+                while (remaining) {
+
+                    // up to four adapters per round: their rows of B are requested together
+                    int curs[4];
+                    unsigned long long sames[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        if (remaining) {
+                            curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
+                            sames[b] = __ballot(ad_row == curs[b]);
+                            remaining &= ~sames[b];
+                        } else {
+                            curs[b] = curs[0];                 // (a useless request that stays in bounds)
+                            sames[b] = 0;
+                        }
+                    }
+                    u32x4 bf[4][4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) b_request(bf[b], curs[b], kk);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        if (!sames[b]) continue;
+#pragma unroll
+                        for (int mb = 0; mb < 4; ++mb) {
+                            if (!((sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
+                            const bool mine = (sames[b] >> (16 * mb + l16)) & 1ull;
+                            float tv[8];
+                            const float *trow = tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq;
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) tv[i] = mine ? trow[i] : 0.f;
+                            uint4 thi, tlo;
+                            split_bf16(tv, thi, tlo);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const uint4 b4 = k_ok ? __builtin_bit_cast(uint4, bf[b][j]) : make_uint4(0, 0, 0, 0);
+                                acc[mb][j] = mfma16(thi, b4, acc[mb][j]);
+                                acc[mb][j] = mfma16(tlo, b4, acc[mb][j]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    MLORA_TRACE_POINT(trace_slot, 4);
+    if (tile_ok) {
+        const bool full = tile * TILE_N + TILE_N <= N;
+        if (full) {
+
+            // rows of 64 outputs through a wave-private LDS buffer, so that a lane stores 16
+            // neighbouring columns at once instead of 64 single values
+            float *st = lds.stage[wave];
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) st[(4 * lq + e) * (TILE_N + 4) + 16 * j + l16] = acc[mb][j][e];
+                const int row = lane >> 2, c0 = (lane & 3) * 16;
+                const int m = m0 + 16 * mb + row;
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(st + row * (TILE_N + 4) + c0);
+                f32x4 o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o[q] = src[q];
+                if (m < M) {
+                    const size_t at = (size_t)m * N + tile * TILE_N + c0;
+                    if (a.y_fp32) {
+                        f32x4 *dst = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(P.y) + at);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) dst[q] = o[q];
+                    } else {
+                        u32x4 pk[2];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t lo2 = float_to_bf16_bits(o[q][0]) | ((uint32_t)float_to_bf16_bits(o[q][1]) << 16);
+                            const uint32_t hi2 = float_to_bf16_bits(o[q][2]) | ((uint32_t)float_to_bf16_bits(o[q][3]) << 16);
+                            pk[q >> 1][(q & 1) * 2] = lo2;
+                            pk[q >> 1][(q & 1) * 2 + 1] = hi2;
+                        }
+                        u32x4 *dst = reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(P.y) + at);
+                        dst[0] = pk[0];
+                        dst[1] = pk[1];
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = m0 + 16 * mb + 4 * lq + e;
+                    if (m >= M) continue;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int n = tile * TILE_N + 16 * j + l16;
+                        if (n >= N) continue;
+                        if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = acc[mb][j][e];
+                        else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(acc[mb][j][e]);
+                    }
+                }
+        }
+    }
+    MLORA_TRACE_POINT(trace_slot, 5);
+
+    // counters back to zero for the next call (every wave owns the counters of its tile)
+    if (tile_ok && lane == 0) {
+        if (need_p) __hip_atomic_store(pctr, 0u, 0, 4);
+        if (need_s) {
+            const int users = P.n_finish_blocks / copies + (fin % copies < P.n_finish_blocks % copies ? 1 : 0);
+            if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
+                __hip_atomic_store(sctr, 0u, 0, 4);
+                __hip_atomic_store(sctr + 1, 0u, 0, 4);
+            }
+        }
+    }
+}
+
+constexpr int wide_lds_bytes()
+{
+    return sizeof(WideLds) > sizeof(ShrinkLds) ? (int)sizeof(WideLds) : (int)sizeof(ShrinkLds);
+}
+
+template <int SPG>
+__global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
+{
+    __shared__ __align__(16) unsigned char smem[wide_lds_bytes()];
+    const int b = (int)blockIdx.x;
+    int first;
+    if (b < a.shrink_blocks) {
+        if (blockIdx.y != 0) return;
+        const int pi = find_proj(a.shrink_begin, b, first);
+        shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        return;
+    }
+    WideLds &lds = *reinterpret_cast<WideLds *>(smem);
+    const int m0 = (int)blockIdx.y * WIDE_ROWS;
+    if (b < a.shrink_blocks + a.pre_base_blocks) {
+        const int pb = b - a.shrink_blocks;
+        const int pi = find_proj(a.pre_begin, pb, first);
+        const ProjArgs P = fetch_proj(a, pi);
+        const int local = pb - first;
+        const int groups = (tiles_n(P.N) + WIDE_TILES - 1) / WIDE_TILES;
+        wide_unit<SPG>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
+    } else {
+        const int mb_ = b - a.shrink_blocks - a.pre_base_blocks;
+        const int pi = find_proj(a.main_begin, mb_, first);
+        const ProjArgs P = fetch_proj(a, pi);
+        wide_unit<SPG>(a, P, pi, mb_ - first, 0, m0, lds);
+    }
+}
+
 template <int MB, int XR>
 static hipError_t launch_instance(const LayerArgs &a, int n_blocks, hipStream_t s)
 {
@@ -1072,6 +1555,14 @@ static hipError_t launch_instance(const LayerArgs &a, int n_blocks, hipStream_t 
 
 hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s)
 {
+    if (a.M >= WIDE_MIN_ROWS) {
+        const dim3 grid((unsigned)n_blocks, (unsigned)(a.m_pad / rows_per_chunk(a.M)));
+        // (the host puts only projections with the same group size into one wide launch)
+        if (a.p[0].spg == 1)      wide_kernel<1><<<grid, dim3(256), 0, s>>>(a);
+        else if (a.p[0].spg == 2) wide_kernel<2><<<grid, dim3(256), 0, s>>>(a);
+        else                      wide_kernel<4><<<grid, dim3(256), 0, s>>>(a);
+        return hipGetLastError();
+    }
     if (a.M <= 8)  return launch_instance<1, 8>(a, n_blocks, s);
     if (a.M <= 16) return launch_instance<1, 16>(a, n_blocks, s);
     if (a.M <= 24) return launch_instance<2, 24>(a, n_blocks, s);

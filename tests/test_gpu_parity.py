@@ -37,7 +37,7 @@ def control_bytes(shapes, M):
     """Size of the status word + completion counters at the head of a workspace (one launch of
     up to 16 projections): 16 x 16 counter lines of 128 bytes and one more per (column tile, row
     chunk) of every projection whose K is cut into more than one unit of 2048 inputs."""
-    rpc = 16 if M <= 16 else 32
+    rpc = 16 if M <= 16 else 32 if M < 64 else 64
     chunks = -(-M // rpc)
     n = sum(-(-s.N // 64) * chunks for s in shapes if -(-(s.K // 128) // 16) > 1)
     return 256 + (16 * 16 + n) * 128
