@@ -1500,12 +1500,12 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 
     // counters back to zero for the next call (every wave owns the counters of its tile)
     if (tile_ok && lane == 0) {
-        if (need_p) __hip_atomic_store(pctr, 0u, 0, 4);
+        if (need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (need_s) {
             const int users = P.n_finish_blocks / copies + (fin % copies < P.n_finish_blocks % copies ? 1 : 0);
             if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
-                __hip_atomic_store(sctr, 0u, 0, 4);
-                __hip_atomic_store(sctr + 1, 0u, 0, 4);
+                __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
