@@ -266,7 +266,9 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             d.spg = p.group / KSTEP;
             d.alpha = p.alpha;
             d.ksplit = ksplit_of(p, M, lb);
-            d.n_finish_blocks = tiles_n(p.N) * chunks;
+            // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
+            // finishing ones, or every K unit where the LoRA term is spread over them
+            d.n_finish_blocks = tiles_n(p.N) * chunks * (M >= WIDE_MIN_ROWS ? d.ksplit : 1);
             // base blocks: one per column tile, or per four of them for 64 rows and more
             const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
             a.main_begin[i] = main_blocks;

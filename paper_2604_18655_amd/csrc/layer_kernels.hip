@@ -1218,12 +1218,17 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + wave + (int)blockIdx.y * (int)gridDim.x * 4;
     MLORA_TRACE_POINT(trace_slot, 0);
-    const bool lora = ku == 0 && a.row_adapter != nullptr && P.n_adapters > 0;
+    // Every K unit of a tile takes a share of the LoRA term (the adapters of the chunk are dealt
+    // out to the units in turn): the rows of B of many adapters are more than the finishing
+    // blocks alone can fetch in good time.  So every unit waits for the shrink blocks, and
+    // P.n_finish_blocks counts (tile, chunk, unit) triples here.
+    const bool lora = a.row_adapter != nullptr && P.n_adapters > 0;
     const int rows_here = min(WIDE_ROWS, M - m0);
     const int chunk = m0 / WIDE_ROWS, chunks = a.m_pad / WIDE_ROWS;
     const int fin = tile * chunks + chunk;
+    const int user = fin * P.ksplit + ku;
     const int copies = min(CTR_REPL, P.n_finish_blocks);
-    unsigned *const sctr = a.ctrl + shrink_ctr(pi, fin % copies);
+    unsigned *const sctr = a.ctrl + shrink_ctr(pi, user % copies);
     unsigned *const pctr = a.ctrl + P.part_ctr + fin * CTR_STRIDE;
     const bool need_s = lora, need_p = ku == 0 && P.ksplit > 1;
 
@@ -1264,7 +1269,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     MLORA_TRACE_POINT(trace_slot, 7);
 #pragma nounroll
     for (int ss = 0; ss < unit_cnt; ss += 2) {
-
         // stage ss: set A, x buffer 0
         __syncthreads();                                   // its rows of x are in place; buffer 1 is free
 #pragma unroll
@@ -1295,41 +1299,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             for (int e = 0; e < 4; ++e) acc[mb][j][e] *= prev[j];
 
     // element (mb, j, e) of this lane: row 16*mb + 4*lq + e of the chunk, column 16*j + l16 of the tile
-    if (ku > 0) {
-        if (tile_ok) {
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) store_shared(dst + 16 * j, acc[mb][j][e]);
-                }
-            __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's stores have completed
-            if (lane == 0) atomicAdd(pctr, 1u);
-        }
-        return;
-    }
-
-    // what this wave's tile needs from other blocks
-    if (tile_ok) {
-        bool ok = true;
-        if (need_s) ok = wait_count(sctr, (unsigned)P.n_shrink_blocks);
-        if (need_p) ok = wait_count(pctr, (unsigned)(P.ksplit - 1)) && ok;
-        if (!ok && lane == 0) atomicOr(a.status, 1u);
-        if (need_p) {
-            for (int u = 0; u + 1 < P.ksplit; ++u)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[mb][j][e] += load_shared(src + 16 * j);
-                    }
-        }
-    }
-    MLORA_TRACE_POINT(trace_slot, 8);
+    if (tile_ok && need_s && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
     if (lora) {                                            // (uniform over the block)
         // a spare wave has not looked at the shrink counter: it must, before it reads t
 
@@ -1375,7 +1345,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         __syncthreads();
         MLORA_TRACE_POINT(trace_slot, 3);
         if (tile_ok) {
-
             // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
             // tile's 64 columns are fetched once and used by every block of 16 rows that holds
             // such a row.  Four adapters are fetched per round trip.
@@ -1394,19 +1363,26 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             for (int kk = 0; kk < r32 / 32; ++kk) {
                 const bool k_ok = 32 * kk + 8 * lq < P.rank;
                 unsigned long long remaining = all;
+                int ordinal = 0;                               // of the adapter among those of the chunk
                 while (remaining) {
-
                     // up to four adapters per round: their rows of B are requested together
                     int curs[4];
                     unsigned long long sames[4];
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
+                        // skip the adapters that other K units of this tile look after
+                        while (remaining && ordinal % P.ksplit != ku) {
+                            const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
+                            remaining &= ~__ballot(ad_row == other);
+                            ++ordinal;
+                        }
                         if (remaining) {
                             curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
                             sames[b] = __ballot(ad_row == curs[b]);
                             remaining &= ~sames[b];
+                            ++ordinal;
                         } else {
-                            curs[b] = curs[0];                 // (a useless request that stays in bounds)
+                            curs[b] = b ? curs[0] : 0;         // (a useless request that stays in bounds)
                             sames[b] = 0;
                         }
                     }
@@ -1439,10 +1415,35 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         }
     }
     MLORA_TRACE_POINT(trace_slot, 4);
-    if (tile_ok) {
+    if (ku > 0) {
+        if (tile_ok) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) store_shared(dst + 16 * j, acc[mb][j][e]);
+                }
+            __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's stores have completed
+            if (lane == 0) atomicAdd(pctr, 1u);
+        }
+    } else if (tile_ok && need_p) {
+        if (!wait_count(pctr, (unsigned)(P.ksplit - 1)) && lane == 0) atomicOr(a.status, 1u);
+        for (int u = 0; u + 1 < P.ksplit; ++u)
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[mb][j][e] += load_shared(src + 16 * j);
+                }
+    }
+    MLORA_TRACE_POINT(trace_slot, 8);
+    if (tile_ok && ku == 0) {
         const bool full = tile * TILE_N + TILE_N <= N;
         if (full) {
-
             // rows of 64 outputs through a wave-private LDS buffer, so that a lane stores 16
             // neighbouring columns at once instead of 64 single values
             float *st = lds.stage[wave];
@@ -1502,7 +1503,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     if (tile_ok && lane == 0) {
         if (need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (need_s) {
-            const int users = P.n_finish_blocks / copies + (fin % copies < P.n_finish_blocks % copies ? 1 : 0);
+            const int users = P.n_finish_blocks / copies + (user % copies < P.n_finish_blocks % copies ? 1 : 0);
             if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
                 __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
