@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0          # dense bf16, MI355X
 CACHE_BYTES = 256 << 20
 METRIC = "µs per multi-LoRA W4 linear + achieved HBM GB/s (% of 8 TB/s), 1 MI355X"
 
@@ -38,7 +39,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", help="c2 (default), c1, c3, c4_decode, c5_up, c5_down")
+    ap.add_argument("--workload", default="c2", help="c2 (default), c1, c3, c4_decode, c4_prefill, c5_up, c5_down")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
                          "eager: one library call per step from Python")
@@ -151,7 +152,11 @@ def main():
     kern_ms = ev0.elapsed_time(ev1) / n_ev
     base_bytes = step_bytes / launches_per_step
     achieved = base_bytes / (kern_ms * 1e-3) / 1e9
-    kernel_name = "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
+    wide = M >= 64                       # the library's kernel for 64 rows and more: bounded by the matrix units
+    spg = w.projs[0].group // 32
+    kernel_name = ("wide_kernel<%d>" % spg) if wide else \
+        "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
+    achieved_tflops = (step_flops / launches_per_step) / (kern_ms * 1e-3) / 1e12
 
     result = {
         "metric": METRIC,
@@ -182,11 +187,12 @@ def main():
         "setup_s": round(setup_s, 1),
         "roofline": {
             "kernel": kernel_name,
-            "bound": "hbm",
-            "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "bound": "mfma" if wide else "hbm",
+            "achieved": round(achieved_tflops, 1) if wide else round(achieved, 1),
+            "peak": MFMA_BF16_PEAK_TFLOPS if wide else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if wide else "GB/s",
+            "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4) if wide else round(achieved / HBM_PEAK_GBS, 4),
+            "hbm_gbs": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": MEASURED_TRAFFIC.get(w.key),
             "algorithmic_bytes_per_launch": int(base_bytes),
             "avg_launch_us": round(kern_ms * 1e3, 3),

@@ -179,6 +179,55 @@ def test_ragged_shapes(gpu, K, N, G, r, n_ad, M):
     check_linear(gpu, prob, x, rows, f"K{K} N{N} G{G} r{r} a{n_ad} M{M}")
 
 
+@pytest.mark.parametrize("K,N,G,r,n_ad,M", [
+    (128, 64, 32, 8, 2, 64),        # one super-step, one tile (three spare waves), exactly one chunk
+    (384, 200, 64, 24, 3, 65),      # ragged N inside the fourth tile, one row in the second chunk
+    (640, 328, 128, 128, 5, 100),   # six tiles (two blocks of columns), maximum rank, odd super-steps
+    (2304, 96, 32, 40, 7, 129),     # small launch: K cut into units, rank not a multiple of 16
+    (512, 1024, 32, 16, 40, 200),   # more adapters than rows of a 16-row block, four full blocks
+])
+def test_wide_shapes(gpu, K, N, G, r, n_ad, M):
+    """64 rows and more take the kernel with 64 x 256 blocks: ragged tiles, chunks and ranks."""
+    prob = random_problem(K + N + M, K, N, G, r, n_ad)
+    rng = np.random.default_rng(M)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    rows = rng.integers(-1, n_ad, size=M).astype(np.int32)
+    check_linear(gpu, prob, x, rows, f"wide K{K} N{N} G{G} r{r} a{n_ad} M{M}")
+    # rows grouped by adapter, all rows without adapter, no row index at all
+    check_linear(gpu, prob, x, np.sort(rows), "wide, grouped rows")
+    check_linear(gpu, prob, x, np.full(M, -1, np.int32), "wide, base only")
+    y = run_linear(gpu, prob, x, None, 1)
+    y_base = run_linear(gpu, prob, x, np.full(M, -1, np.int32), 1)
+    assert np.array_equal(y, y_base)
+
+
+def test_wide_extreme_and_zero_scales(gpu):
+    """The wide kernel keeps its accumulators in units of the current group's scale: scales that
+    jump by many orders of magnitude between groups, and zero scales, must not disturb it."""
+    K, N, G, M = 1024, 128, 32, 64
+    rng = np.random.default_rng(5)
+    codes = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    codes[::3] = 7
+    codes[1::3] = -8
+    groups = K // G
+    sc = np.empty((N, groups), np.float16)
+    sc[:, 0::4] = np.float16(0.5)
+    sc[:, 1::4] = np.float16(6.1e-5)
+    sc[:, 2::4] = np.float16(0.0)                 # dead groups: contribute exactly nothing
+    sc[:, 3::4] = np.float16(2.0e-2)
+    sc[5, :] = np.float16(0.0)                    # a column that is dead throughout
+    sc[6, :3] = np.float16(0.0)                   # a column that starts dead
+    sc[7, 0] = np.float16(8.0)                    # large then tiny
+    shape = wl.ProjShape("e", K, N, G, 16, 2, 1.0)
+    prob = wl.Problem(shape, wl.pack_nibbles(codes), sc.view(np.uint16),
+                      wl.f32_to_bf16_bits(rng.standard_normal((2, 16, K)).astype(np.float32) / 32),
+                      wl.f32_to_bf16_bits(rng.standard_normal((2, N, 16)).astype(np.float32)))
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, ::7] *= np.float32(1e-3)
+    rows = rng.integers(-1, 2, size=M).astype(np.int32)
+    check_linear(gpu, prob, wl.f32_to_bf16_bits(x), rows, "wide extreme")
+
+
 def test_extreme_codes_and_scales(gpu):
     # all codes -8 / +7, large and tiny scales, x with large dynamic range
     K, N, G, M = 256, 64, 32, 4
