@@ -31,7 +31,7 @@ METRIC = "µs per multi-LoRA W4 linear + achieved HBM GB/s (% of 8 TB/s), 1 MI35
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by a copy kernel of known size; see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"c2": 49234022}     # bytes per launch: profiles/layer_kernel_c2_hbm_traffic.txt
 
 
 def parse_args():
@@ -45,6 +45,10 @@ def parse_args():
                          "eager: one library call per step from Python")
     ap.add_argument("--copies", type=int, default=0, help="rotating copies (0 = enough to defeat the cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device-to-device copies of 256 MiB (torch clone): a kernel of "
+                         "known traffic next to which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings "
+                         "of the layer kernel can be scaled")
     ap.add_argument("--y-fp32", action="store_true")
     return ap.parse_args()
 
@@ -107,6 +111,14 @@ def main():
         base = (i % copies) * calls_per_step
         for l in range(calls_per_step):
             plans[base + l].run(stream)
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        src.fill_(1)
+        for _ in range(4):
+            dst = src.clone()             # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up, then the timed region: exactly K steps between two synchronisations
     for i in range(args.warmup):
