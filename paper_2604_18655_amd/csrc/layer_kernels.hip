@@ -1047,19 +1047,16 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     }
     const BaseLdsOf<MB, XR> lds{smem};
     const int m0 = (int)blockIdx.y * 16 * MB;
-    if (b < a.shrink_blocks + a.pre_base_blocks) {
-        const int pb = b - a.shrink_blocks;
-        const int pi = find_proj(a.pre_begin, pb, first);
-        const ProjArgs P = fetch_proj(a, pi);
-        const int local = pb - first;
-        const int tiles = tiles_n(P.N);
-        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, local % tiles, 1 + local / tiles, m0, lds);
-    } else {
-        const int mb_ = b - a.shrink_blocks - a.pre_base_blocks;
-        const int pi = find_proj(a.main_begin, mb_, first);
-        const ProjArgs P = fetch_proj(a, pi);
-        base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, mb_ - first, 0, m0, lds);
-    }
+    // (one call site for both kinds of base block: the kernel's code is large, and what runs
+    // once per launch is paid for by instruction fetch)
+    const bool pre = b < a.shrink_blocks + a.pre_base_blocks;
+    const int bb = b - a.shrink_blocks - (pre ? 0 : a.pre_base_blocks);
+    const int pi = pre ? find_proj(a.pre_begin, bb, first) : find_proj(a.main_begin, bb, first);
+    const ProjArgs P = fetch_proj(a, pi);
+    const int local = bb - first;
+    const int tiles = tiles_n(P.N);
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, pre ? local % tiles : local,
+                                                      pre ? 1 + local / tiles : 0, m0, lds);
 }
 
 // ------------------------------------------------------------------------------------------
