@@ -286,6 +286,45 @@ def layer_on_gpu(gpu, probs, xs, rows, y_dtype):
     return [device.y_to_numpy(y) for y in ys]
 
 
+@pytest.mark.parametrize("M", [5, 40, 72])
+def test_layer_step_many_projections_mixed_groups(gpu, M):
+    """More projections than one launch holds (16), group sizes mixed (64 rows and more: a launch
+    per run of equal group size), with and without split K, some without adapters."""
+    lib, device, torch = gpu
+    rng = np.random.default_rng(100 + M)
+    shapes = []
+    for i in range(19):
+        K = [256, 384, 2304, 128][i % 4]
+        N = [64, 200, 96, 130][(i // 2) % 4]
+        G = [32, 64, 128][i % 3] if i % 5 else 32
+        r = [8, 16, 24, 64][i % 4]
+        n_ad = 0 if i == 7 else 4
+        shapes.append(wl.ProjShape(f"p{i}", K, N, G, r, n_ad, 1.5))
+    probs = [wl.make_problem(s, 77, 0, i) for i, s in enumerate(shapes)]
+    xs_by_k = {K: wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)) for K in {s.K for s in shapes}}
+    xs = [xs_by_k[s.K] for s in shapes]
+    rows = rng.integers(-1, 4, size=M).astype(np.int32)
+    ys = layer_on_gpu(gpu, probs, xs, rows, 1)
+    for p, x, y in zip(probs, xs, ys):
+        ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x,
+                            rows if p.shape.n_adapters else None)
+        assert rel_err(y, ref) <= TOL_F32, p.shape.name
+
+
+def test_maximum_rows(gpu):
+    """M = 4096, the most rows a call takes: 64 chunks of the wide kernel; oracle on sampled rows."""
+    K, N, G, r, n_ad, M = 256, 136, 64, 16, 3, 4096
+    prob = random_problem(4096, K, N, G, r, n_ad)
+    rng = np.random.default_rng(4096)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    rows = rng.integers(-1, n_ad, size=M).astype(np.int32)
+    y = run_linear(gpu, prob, x, rows, 1)
+    sel = np.concatenate([np.arange(0, 70), rng.choice(M, 200, replace=False), np.arange(M - 70, M)])
+    ref = oracle.linear(prob.wq, prob.scales, G, prob.lora_a, prob.lora_b, prob.shape.alpha,
+                        np.ascontiguousarray(x[sel]), np.ascontiguousarray(rows[sel]))
+    assert rel_err(y[sel], ref) <= TOL_F32
+
+
 def test_workspace_reuse_and_graph_replay_match_first_call(gpu):
     """One workspace serves call after call (the counters reset themselves), eagerly and as a
     captured graph replayed several times with eager work in between: every result equals the
