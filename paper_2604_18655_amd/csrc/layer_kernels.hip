@@ -257,9 +257,14 @@ __device__ __forceinline__ void stream_request(StreamRegs &r, const u32x4 *wp0, 
     const u32x4 *wn = wp0 + (in ? (size_t)ss * 256 + lane : 0);
     const uint2 *sn = sp0 + (in ? (size_t)ss * gs * 16 + (lane & 15) : 0);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) r.w[u] = wn[in ? u * 64 : 0];
+    for (int u = 0; u < 4; ++u) r.w[u] = __builtin_nontemporal_load(wn + (in ? u * 64 : 0));
 #pragma unroll
-    for (int g = 0; g < 4; ++g) r.sc[g] = sn[in ? min(g, gs - 1) * 16 : 0];
+    for (int g = 0; g < 4; ++g) {
+        // (the scales' type is HIP's struct, which the builtin does not take: read as two words)
+        const unsigned long long v = __builtin_nontemporal_load(
+            reinterpret_cast<const unsigned long long *>(sn + (in ? min(g, gs - 1) * 16 : 0)));
+        r.sc[g] = make_uint2((unsigned)v, (unsigned)(v >> 32));
+    }
 }
 
 // The math of one super-step; xs = this lane's row of x in LDS at the super-step's first k-step.
