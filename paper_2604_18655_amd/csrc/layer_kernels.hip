@@ -129,7 +129,7 @@ __device__ __forceinline__ void round_issue_w(RoundRegs<XR, R> &rr, const uint4 
 {
     const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (size_t)ks * 64 + lane;
 #pragma unroll
-    for (int i = 0; i < R; ++i) rr.w[i] = wp[i * 64];
+    for (int i = 0; i < R; ++i) rr.w[i] = __builtin_nontemporal_load(wp + i * 64);   // (read once)
 }
 
 // Request the rows of x (clamped to the row) and the scales of one round.
@@ -1111,7 +1111,7 @@ __device__ __forceinline__ void wide_request(WideRegs &r, const u32x4 *wp0, cons
     const u32x4 *wn = wp0 + (in ? (size_t)ss * 256 + lane : 0);
     const uint2 *sn = sp0 + (in ? (size_t)ss * gs * 16 + (lane & 15) : 0);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) r.w[u] = wn[in ? u * 64 : 0];
+    for (int u = 0; u < 4; ++u) r.w[u] = __builtin_nontemporal_load(wn + (in ? u * 64 : 0));   // (read once)
 #pragma unroll
     for (int g = 0; g < 4; ++g) r.sc[g] = sn[in ? min(g, gs - 1) * 16 : 0];
 }
