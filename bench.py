@@ -218,7 +218,7 @@ def main():
         probs, xs, rows = host_sets[0]
         cores = oracle.max_threads()
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 50:
+        while t_cpu < 10.0 and reps < 1000:
             t1 = time.perf_counter()
             for p, x in zip(probs, xs):
                 oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows)
