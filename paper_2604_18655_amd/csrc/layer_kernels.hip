@@ -334,28 +334,30 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[4], StreamRegs &ra, Str
 // Loads the epilogue needs that do not depend on other blocks, requested ahead of their use (all
 // unconditional; a thread with nothing to fetch re-reads a valid address).  The N outputs of a
 // thread lie in one row, 16 columns apart, so their rows of B differ by a fixed stride.
-template <int N>
+template <int N, int MBR>
 struct EpiPrefetch {
-    const uint16_t *bad;                     // B of the row's adapter (or a safe address)
-    int brank;                               // rank (0 with the safe address: every offset is 0)
+    const uint16_t *bad[MBR];                // B of each row's adapter (or a safe address)
+    int brank[MBR];                          // rank (0 with the safe address: every offset is 0)
     int n0, nlast;                           // column of output 0; last valid column
-    const float *tp;                         // this thread's entry of t_part[0] (or a safe address)
-    size_t tstride;                          // distance between K chunks of t_part
+    // entries of t this thread sums: row t_ml + 16 * i, rank index t_jj
+    const float *tp[MBR];                    // the entry in t_part[0] (or a safe address)
+    size_t tstride[MBR];                     // distance between K chunks of t_part (0 with the safe address)
     int kch, t_ml, t_jj;
-    bool t_mine;
+    bool t_mine[MBR];
     uint4 b[N > 0 ? N : 1][2];
     __device__ __forceinline__ void issue()
     {
-        // the address passes through an empty asm: without it the compiler hoists these loads to
-        // the top of the kernel and then spills their results across the whole K loop
-        asm volatile("" : "+v"(bad));
-        const int second = brank > 8 ? 8 : 0;
         // (global, not generic, loads: a generic load also counts as an LDS access, and every
         // later wait for LDS would wait for these as well)
         using G = const __attribute__((address_space(1))) u32x4;
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            const uint16_t *row = bad + (unsigned)(min(n0 + 16 * q, nlast) * brank);
+            const int mb = q >> 2;
+            // the address passes through an empty asm: without it the compiler hoists these loads
+            // to the top of the kernel and then spills their results across the whole K loop
+            if ((q & 3) == 0) asm volatile("" : "+v"(bad[mb]));
+            const int second = brank[mb] > 8 ? 8 : 0;
+            const uint16_t *row = bad[mb] + (unsigned)(min(n0 + 16 * (q & 3), nlast) * brank[mb]);
             b[q][0] = __builtin_bit_cast(uint4, *(G *)(row));
             b[q][1] = __builtin_bit_cast(uint4, *(G *)(row + second));
         }
@@ -437,8 +439,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     // what this thread will finish, and the adapter of each of its rows
     const bool lora = (ku == 0) && (a.row_adapter != nullptr) && (P.n_adapters > 0);
     const int rows_here = min(ROWS, M - m0);
-    constexpr bool PREFETCH = EPT <= 4;                    // more outputs per thread: too many registers
-    const bool fast = PREFETCH && lora && P.rank <= FAST_RANK && rows_here * P.r16 <= NT;
+    constexpr bool PREFETCH = EPT <= 8;                    // more outputs per thread: too many registers
+    // (ranks up to FAST_RANK: r16 == 16, and the chunk's entries of t number at most MB per thread)
+    const bool fast = PREFETCH && lora && P.rank <= FAST_RANK;
     // element qq of this thread: tile row and column (cheap to recompute, so not kept live)
     static_assert(WAVES == 4, "one wave per element of an MFMA result register");
     auto elem_ml = [&](int qq) { return (qq >> 2) * 16 + 4 * lq + wave; };
@@ -460,23 +463,59 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 
     // epilogue operands fetched while the last round is being computed: the rows of B of this
     // thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
-    EpiPrefetch<PREFETCH ? EPT : 0> pf;
+    EpiPrefetch<PREFETCH ? EPT : 0, MB> pf;
     auto prefetch_setup = [&]() {
-        pf.t_ml = tid >> 4;                                // (fast: r16 == 16)
+        pf.t_ml = tid >> 4;
         pf.t_jj = tid & 15;
-        pf.t_mine = fast && tid < rows_here * P.r16;
-        {
-            const int ad = elem_ad(0);                     // (PREFETCH: one row per thread)
-            const bool ok = fast && ad >= 0;
-            pf.bad = ok ? P.lora_b + (size_t)ad * N * P.rank : reinterpret_cast<const uint16_t *>(P.codes);
-            pf.brank = ok ? P.rank : 0;
-            pf.n0 = tile * TILE_N + l16;
-            pf.nlast = N - 1;
-        }
-        pf.tp = pf.t_mine ? P.t_part + (size_t)(m0 + pf.t_ml) * P.r16 + pf.t_jj
-                          : reinterpret_cast<const float *>(P.codes);
-        pf.tstride = pf.t_mine ? (size_t)M * P.r16 : 0;
+        pf.n0 = tile * TILE_N + l16;
+        pf.nlast = N - 1;
         pf.kch = P.kch;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int ad = elem_ad(4 * i);
+            const bool ok = fast && ad >= 0;
+            pf.bad[i] = ok ? P.lora_b + (size_t)ad * N * P.rank : reinterpret_cast<const uint16_t *>(P.codes);
+            pf.brank[i] = ok ? P.rank : 0;
+            pf.t_mine[i] = fast && pf.t_ml + 16 * i < rows_here;
+            pf.tp[i] = pf.t_mine[i] ? P.t_part + (size_t)(m0 + pf.t_ml + 16 * i) * P.r16 + pf.t_jj
+                                    : reinterpret_cast<const float *>(P.codes);
+            pf.tstride[i] = pf.t_mine[i] ? (size_t)M * P.r16 : 0;
+        }
+    };
+    // alpha * t of this thread's entries -> LDS: the K-chunk partials of the shrink step, all
+    // requested at once and summed in fixed order
+    auto t_entries_to_lds = [&]() {
+        float ts[MB];
+        if (pf.kch <= 4) {
+            float tv[MB][4];
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc)
+                    tv[i][kc] = load_shared(pf.tp[i] + (size_t)min(kc, pf.kch - 1) * pf.tstride[i]);
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                ts[i] = 0.f;
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc) ts[i] += kc < pf.kch ? tv[i][kc] : 0.f;
+            }
+        } else {
+            float tv[MB][MAX_KCHUNKS];
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCHUNKS; ++kc)
+                    tv[i][kc] = load_shared(pf.tp[i] + (size_t)min(kc, pf.kch - 1) * pf.tstride[i]);
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                ts[i] = 0.f;
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) ts[i] += kc < pf.kch ? tv[i][kc] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            if (pf.t_mine[i]) lds.t_row(pf.t_ml + 16 * i)[pf.t_jj] = ts[i] * P.alpha;
     };
 
     // the two constants of expand_codes arrive as kernel arguments so that they live in
@@ -554,14 +593,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             MLORA_TRACE_POINT(trace_slot, 7);
             const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
             round_to_lds<XR, R>(ra, buf, lane);
-            // epilogue operands: requested as soon as the first round's registers are free, in
-            // flight while both rounds are computed.  (The empty asm keeps the decoding of the
-            // adapter indices, and with it the wait for their loads, from being hoisted.)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(ad_raw[mb]));
-            prefetch_setup();
-            pf.issue();
-            __builtin_amdgcn_sched_barrier(0);
             if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, na, rows_x, mask, bias, lane);
             else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, na, rows_x, mask, bias, lane);
             else                 round_compute<MB, XR, R, 4>(acc, buf, na, rows_x, mask, bias, lane);
@@ -571,6 +602,12 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, nb, rows_x, mask, bias, lane);
             else                 round_compute<MB, XR, R, 4>(acc, buf, nb, rows_x, mask, bias, lane);
         }
+        // rows of B: requested once the rounds' registers are free.  (The empty asm keeps the
+        // decoding of the adapter indices, and with it the wait for their loads, behind the loop.)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(ad_raw[mb]));
+        prefetch_setup();
+        pf.issue();
     }
 
     MLORA_TRACE_POINT(trace_slot, 2);
@@ -606,77 +643,64 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const bool lean = PREFETCH && ku == 0 && (!lora || fast) && P.ksplit <= PU + 1;
     if (lean) {
         if constexpr (PREFETCH) {
-            const int m = m0 + elem_ml(0);
-            // this thread's entry of t: K-chunk partials of the shrink step, summed in fixed order
-            if (lora) {
-                float ts = 0.f;
-                if (pf.kch <= 4) {
-                    float tv[4];
-#pragma unroll
-                    for (int kc = 0; kc < 4; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
-#pragma unroll
-                    for (int kc = 0; kc < 4; ++kc) ts += kc < pf.kch ? tv[kc] : 0.f;
-                } else {
-                    float tv[MAX_KCHUNKS];
-#pragma unroll
-                    for (int kc = 0; kc < MAX_KCHUNKS; ++kc)
-                        tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
-#pragma unroll
-                    for (int kc = 0; kc < MAX_KCHUNKS; ++kc) ts += kc < pf.kch ? tv[kc] : 0.f;
-                }
-                if (pf.t_mine) lds.t_row(pf.t_ml)[pf.t_jj] = ts * P.alpha;
-            }
+            if (lora) t_entries_to_lds();
             float pv[EPT][PU];
             if (P.ksplit > 1) {
-                const float *src = P.partial + ((size_t)tile * a.m_pad + min(m, M - 1)) * TILE_N + l16;
                 const size_t ustride = (size_t)tiles * a.m_pad * TILE_N;
 #pragma unroll
-                for (int qq = 0; qq < EPT; ++qq)
+                for (int qq = 0; qq < EPT; ++qq) {
+                    const int m = min(m0 + elem_ml(qq), M - 1);
+                    const float *src = P.partial + ((size_t)tile * a.m_pad + m) * TILE_N + elem_col(qq);
 #pragma unroll
-                    for (int u = 0; u < PU; ++u)
-                        pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride + 16 * qq);
+                    for (int u = 0; u < PU; ++u) pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride);
+                }
             }
             MLORA_TRACE_POINT(trace_slot, 3);
             __syncthreads();
             MLORA_TRACE_POINT(trace_slot, 4);
-            f32x4 v = *reinterpret_cast<const f32x4 *>(lds.red(0) + red_at(0, wave, lane));
+            const int n0 = tile * TILE_N + l16;
 #pragma unroll
-            for (int w = 1; w < WAVES; ++w) v += *reinterpret_cast<const f32x4 *>(lds.red(w) + red_at(0, wave, lane));
-            if (P.ksplit > 1) {
+            for (int mb = 0; mb < MB; ++mb) {
+                f32x4 v = *reinterpret_cast<const f32x4 *>(lds.red(0) + red_at(mb, wave, lane));
 #pragma unroll
-                for (int qq = 0; qq < EPT; ++qq)
+                for (int w = 1; w < WAVES; ++w)
+                    v += *reinterpret_cast<const f32x4 *>(lds.red(w) + red_at(mb, wave, lane));
+                if (P.ksplit > 1) {
 #pragma unroll
-                    for (int u = 0; u < PU; ++u) v[qq] += u + 1 < P.ksplit ? pv[qq][u] : 0.f;
-            }
-            if (lora) {
-                float t[FAST_RANK];
-                const f32x4 *tr = reinterpret_cast<const f32x4 *>(lds.t_row(elem_ml(0)));
+                    for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int i = 0; i < FAST_RANK / 4; ++i) {
-                    const f32x4 tq = tr[i];
-                    t[4 * i] = tq[0]; t[4 * i + 1] = tq[1]; t[4 * i + 2] = tq[2]; t[4 * i + 3] = tq[3];
+                        for (int u = 0; u < PU; ++u) v[j] += u + 1 < P.ksplit ? pv[4 * mb + j][u] : 0.f;
                 }
-                const bool mine = elem_ad(0) >= 0;
-                const bool two = P.rank > 8;
+                if (lora) {
+                    float t[FAST_RANK];
+                    const f32x4 *tr = reinterpret_cast<const f32x4 *>(lds.t_row(elem_ml(4 * mb)));
 #pragma unroll
-                for (int qq = 0; qq < EPT; ++qq) {
-                    float l = dot8(pf.b[qq][0], t, 0.f);
-                    if (two) l = dot8(pf.b[qq][1], t + 8, l);
-                    v[qq] += mine ? l : 0.f;
+                    for (int i = 0; i < FAST_RANK / 4; ++i) {
+                        const f32x4 tq = tr[i];
+                        t[4 * i] = tq[0]; t[4 * i + 1] = tq[1]; t[4 * i + 2] = tq[2]; t[4 * i + 3] = tq[3];
+                    }
+                    const bool mine = elem_ad(4 * mb) >= 0;
+                    const bool two = P.rank > 8;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float l = dot8(pf.b[4 * mb + j][0], t, 0.f);
+                        if (two) l = dot8(pf.b[4 * mb + j][1], t + 8, l);
+                        v[j] += mine ? l : 0.f;
+                    }
                 }
-            }
-            if (m < M) {
-                const int n0 = tile * TILE_N + l16;
-                if (a.y_fp32) {
-                    float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;
+                const int m = m0 + elem_ml(4 * mb);
+                if (m < M) {
+                    if (a.y_fp32) {
+                        float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;
 #pragma unroll
-                    for (int qq = 0; qq < EPT; ++qq)
-                        if (n0 + 16 * qq < N) yp[16 * qq] = v[qq];
-                } else {
-                    uint16_t *yp = reinterpret_cast<uint16_t *>(P.y) + (size_t)m * N + n0;
+                        for (int j = 0; j < 4; ++j)
+                            if (n0 + 16 * j < N) yp[16 * j] = v[j];
+                    } else {
+                        uint16_t *yp = reinterpret_cast<uint16_t *>(P.y) + (size_t)m * N + n0;
 #pragma unroll
-                    for (int qq = 0; qq < EPT; ++qq)
-                        if (n0 + 16 * qq < N) yp[16 * qq] = float_to_bf16_bits(v[qq]);
+                        for (int j = 0; j < 4; ++j)
+                            if (n0 + 16 * j < N) yp[16 * j] = float_to_bf16_bits(v[j]);
+                    }
                 }
             }
         }
@@ -695,21 +719,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                                       : reinterpret_cast<const float *>(P.codes);
                 pv[qq][u] = load_shared(src);
             }
-        // one entry of t per thread (K-chunk partials of the shrink step, summed in fixed order)
-        float tv[MAX_KCHUNKS];
-        if (fast) {
-#pragma unroll
-            for (int kc = 0; kc < MAX_KCHUNKS; ++kc) tv[kc] = load_shared(pf.tp + (size_t)min(kc, pf.kch - 1) * pf.tstride);
-        }
-
         // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
         if (fast) {
-            if (pf.t_mine) {
-                float v = 0.f;
-#pragma unroll
-                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) v += kc < P.kch ? tv[kc] : 0.f;
-                lds.t_row(pf.t_ml)[pf.t_jj] = v * P.alpha;
-            }
+            t_entries_to_lds();
         } else if (lora) {
             for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
                 const int ml = idx / P.r16, jj = idx % P.r16;
