@@ -100,9 +100,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // LDS.  The loop is the point of the design: code that runs once is fetched at about 10
 // cycles per instruction (instruction-cache misses), a loop body only on its first pass.
 //
-// Rounds come in pairs: the loads of both rounds of a pair are issued into two register sets
-// before anything is waited for, so a wave keeps 2*R KiB of codes in flight; set A is written
-// to LDS and computed while set B is still arriving.
+// The loads run ahead of the math as a register pipeline: two register sets hold the codes
+// and scales of the next two rounds (they come from HBM: far), one set the rows of x of the
+// next round (from L2: near).  A set goes to LDS as soon as its turn comes and is requested
+// again at once, so a wave has 2*R KiB of codes in flight while it computes.
 // ------------------------------------------------------------------------------------------
 template <int XR, int R>
 struct RoundLds {
@@ -115,53 +116,63 @@ struct RoundLds {
     static constexpr int BYTES = W_BYTES + X_BYTES + SC_BYTES; // per wave
 };
 
-template <int XR, int R>
-struct RoundRegs {
-    u32x4 w[R];                                  // packed codes: from HBM, requested first
-    u32x4 x[RoundLds<XR, R>::NXL];               // rows of x and the scales: small, from L2
-    u32x4 sc;
+template <int R>
+struct RoundW {
+    u32x4 w[R];                                  // packed codes
+    u32x4 sc;                                    // the round's scale groups (up to 8 x 128 bytes)
 };
 
-// Request the codes of one round: k-steps [ks, ks + R) of the tile.  Weight and scale
-// addresses are not clamped (the blob's slack keeps reads past the end in bounds).
 template <int XR, int R>
-__device__ __forceinline__ void round_issue_w(RoundRegs<XR, R> &rr, const uint4 *codes_tile, int ks, int lane)
+struct RoundX {
+    u32x4 x[RoundLds<XR, R>::NXL];
+};
+
+// Request the codes and scales of one round: k-steps [ks, ks + R) of the tile.  A request past
+// the wave's range (!in) becomes a read of the tile's first 16 bytes by every lane: all loads
+// stay unconditional, so the waits the compiler derives stay exact.
+template <int R>
+__device__ __forceinline__ void round_issue_w(RoundW<R> &rw, const uint4 *codes_tile, const uint2 *scales_tile,
+                                              int spg, int ks, bool in, int lane)
 {
-    const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (size_t)ks * 64 + lane;
+    const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (in ? (size_t)ks * 64 + lane : 0);
 #pragma unroll
-    for (int i = 0; i < R; ++i) rr.w[i] = __builtin_nontemporal_load(wp + i * 64);   // (read once)
+    for (int i = 0; i < R; ++i) rw.w[i] = __builtin_nontemporal_load(wp + (in ? i * 64 : 0));   // (read once)
+    // the round's groups are contiguous: 128 bytes each, lane l takes bytes 16*l.. (past the
+    // round's last group the blob's slack keeps the read in bounds)
+    rw.sc = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(scales_tile) +
+                                       (in ? (size_t)(ks / spg) * 8 + lane : 0));
 }
 
-// Request the rows of x (clamped to the row) and the scales of one round.
+// Request the rows of x (clamped to the chunk's rows and to K) of one round.
 template <int XR, int R>
-__device__ __forceinline__ void round_issue_xs(RoundRegs<XR, R> &rr, const uint2 *scales_tile, int spg,
-                                               const uint16_t *x, int K, int m0, int rows_here,
-                                               int ks, int lane)
+__device__ __forceinline__ void round_issue_x(RoundX<XR, R> &rx, const uint16_t *x, int K, int m0, int rows_here,
+                                              int ks, bool in, int lane)
 {
     using L = RoundLds<XR, R>;
+    // (one uniform base and a 32-bit offset per load: eight 64-bit addresses would cost registers)
+    const unsigned char *xb = reinterpret_cast<const unsigned char *>(x + (size_t)m0 * K);
 #pragma unroll
     for (int i = 0; i < L::NXL; ++i) {
         const int byte = i * 1024 + lane * 16;
         const int row = min(byte / L::SEG, rows_here - 1);
         const int k = min(ks * KSTEP + (byte % L::SEG) / 2, K - 8);
-        rr.x[i] = *reinterpret_cast<const u32x4 *>(x + (size_t)(m0 + row) * K + k);
+        const unsigned off = in ? ((unsigned)row * (unsigned)K + (unsigned)k) * 2u : 0u;
+        rx.x[i] = *reinterpret_cast<const u32x4 *>(xb + off);
     }
-    // the round's groups are contiguous: 128 bytes each, lane l takes bytes 16*l..
-    rr.sc = *(reinterpret_cast<const u32x4 *>(scales_tile + (size_t)(ks / spg) * 16) + lane);
 }
 
 template <int XR, int R>
-__device__ __forceinline__ void round_to_lds(const RoundRegs<XR, R> &rr, unsigned char *buf, int lane)
+__device__ __forceinline__ void round_to_lds(const RoundW<R> &rw, const RoundX<XR, R> &rx, unsigned char *buf, int lane)
 {
     using L = RoundLds<XR, R>;
 #pragma unroll
-    for (int i = 0; i < R; ++i) *reinterpret_cast<u32x4 *>(buf + i * 1024 + lane * 16) = rr.w[i];
+    for (int i = 0; i < R; ++i) *reinterpret_cast<u32x4 *>(buf + i * 1024 + lane * 16) = rw.w[i];
 #pragma unroll
     for (int i = 0; i < L::NXL; ++i) {
         const int byte = i * 1024 + lane * 16;
-        *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + (byte / L::SEG) * L::XROW + byte % L::SEG) = rr.x[i];
+        *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + (byte / L::SEG) * L::XROW + byte % L::SEG) = rx.x[i];
     }
-    *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + L::X_BYTES + lane * 16) = rr.sc;
+    *reinterpret_cast<u32x4 *>(buf + L::W_BYTES + L::X_BYTES + lane * 16) = rw.sc;
 }
 
 // Math of one round: n_steps (a multiple of 4) k-steps starting at the front of the buffer.
@@ -576,36 +587,45 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         prefetch_setup();
         pf.issue();
     } else {
-        // K loop: pairs of rounds.  An idle wave (my_cnt == 0) still requests one pair at a valid
-        // place and computes nothing.
-        for (int r0 = 0; r0 < max(ks_total, 1); r0 += 2 * R) {
-            RoundRegs<XR, R> ra, rb;
-            round_issue_w<XR, R>(ra, codes_tile, ks_first + r0, lane);
-            round_issue_xs<XR, R>(ra, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0, lane);
-            round_issue_w<XR, R>(rb, codes_tile, ks_first + r0 + R, lane);
-            round_issue_xs<XR, R>(rb, scales_tile, P.spg, P.x, K, m0, rows_x, ks_first + r0 + R, lane);
-            // adapters of this thread's rows: requested here (unconditionally), decoded when needed
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) ad_raw[mb] = ra_safe[min(m0 + elem_ml(4 * mb), ra_last)];
-            // keep the second round's requests ahead of the first wait: the scheduler would
-            // otherwise sink them below it to save registers, which halves the bytes in flight
+        // K loop, two rounds per pass.  An idle wave (my_cnt == 0) still requests one round at a
+        // valid place and computes nothing.
+        const int nr = ks_total / R;                           // rounds of this wave
+        RoundW<R> wa, wb;
+        RoundX<XR, R> xr;
+        round_issue_w<R>(wa, codes_tile, scales_tile, P.spg, ks_first, true, lane);
+        round_issue_w<R>(wb, codes_tile, scales_tile, P.spg, ks_first + R, 1 < nr, lane);
+        round_issue_x<XR, R>(xr, P.x, K, m0, rows_x, ks_first, true, lane);
+        // (keeps all of these requests ahead of the first wait)
+        __builtin_amdgcn_sched_barrier(0);
+        MLORA_TRACE_POINT(trace_slot, 7);
+        auto compute = [&](int n) {
+            if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, n, rows_x, mask, bias, lane);
+            else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, n, rows_x, mask, bias, lane);
+            else                 round_compute<MB, XR, R, 4>(acc, buf, n, rows_x, mask, bias, lane);
+        };
+#pragma nounroll
+        for (int r0 = 0; r0 < max(nr, 1); r0 += 2) {
+            round_to_lds<XR, R>(wa, xr, buf, lane);
+            round_issue_w<R>(wa, codes_tile, scales_tile, P.spg, ks_first + (r0 + 2) * R, r0 + 2 < nr, lane);
+            round_issue_x<XR, R>(xr, P.x, K, m0, rows_x, ks_first + (r0 + 1) * R, r0 + 1 < nr, lane);
+            // (the scheduler would otherwise sink the requests below the math to save registers)
             __builtin_amdgcn_sched_barrier(0);
-            MLORA_TRACE_POINT(trace_slot, 7);
-            const int na = min(max(ks_total - r0, 0), R), nb = min(max(ks_total - r0 - R, 0), R);
-            round_to_lds<XR, R>(ra, buf, lane);
-            if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, na, rows_x, mask, bias, lane);
-            else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, na, rows_x, mask, bias, lane);
-            else                 round_compute<MB, XR, R, 4>(acc, buf, na, rows_x, mask, bias, lane);
+            compute(r0 < nr ? R : 0);
             MLORA_TRACE_POINT(trace_slot, 6);
-            round_to_lds<XR, R>(rb, buf, lane);
-            if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, nb, rows_x, mask, bias, lane);
-            else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, nb, rows_x, mask, bias, lane);
-            else                 round_compute<MB, XR, R, 4>(acc, buf, nb, rows_x, mask, bias, lane);
+            round_to_lds<XR, R>(wb, xr, buf, lane);
+            round_issue_w<R>(wb, codes_tile, scales_tile, P.spg, ks_first + (r0 + 3) * R, r0 + 3 < nr, lane);
+            round_issue_x<XR, R>(xr, P.x, K, m0, rows_x, ks_first + (r0 + 2) * R, r0 + 2 < nr, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(r0 + 1 < nr ? R : 0);
         }
-        // rows of B: requested once the rounds' registers are free.  (The empty asm keeps the
-        // decoding of the adapter indices, and with it the wait for their loads, behind the loop.)
+        // Everything below derives its indices afresh from the thread id: values shared with the
+        // code above the loop would have to live across it, in registers the loop needs.
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+        // adapters of this thread's rows, then their rows of B: requested once the rounds'
+        // registers are free
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(ad_raw[mb]));
+        for (int mb = 0; mb < MB; ++mb) ad_raw[mb] = ra_safe[min(m0 + elem_ml(4 * mb), ra_last)];
         prefetch_setup();
         pf.issue();
     }
