@@ -139,10 +139,11 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
 // Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
 // library build); each wave appends (constant-rate clock, shader clock) pairs to a buffer.
 #ifdef MLORA_TRACE
-extern __device__ unsigned long long *g_trace;           // [n_waves][32]
+extern __device__ unsigned long long *g_trace;           // [g_trace_slots][32]
+extern __device__ unsigned long long g_trace_slots;      // a wave beyond the buffer records nothing
 #define MLORA_TRACE_POINT(slot, id)                                                        \
     do {                                                                                   \
-        if (g_trace && (threadIdx.x & 63) == 0) {                                          \
+        if (g_trace && (threadIdx.x & 63) == 0 && (unsigned long long)(slot) < g_trace_slots) { \
             g_trace[(size_t)(slot) * 32 + 2 * (id)] = wall_clock64();                      \
             g_trace[(size_t)(slot) * 32 + 2 * (id) + 1] = clock64();                       \
         }                                                                                  \

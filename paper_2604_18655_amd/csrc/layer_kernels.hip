@@ -29,9 +29,12 @@ namespace mlora {
 
 #ifdef MLORA_TRACE
 __device__ unsigned long long *g_trace = nullptr;
-extern "C" hipError_t mlora_trace_set(unsigned long long *p)
+__device__ unsigned long long g_trace_slots = 0;          // waves the buffer has room for
+extern "C" hipError_t mlora_trace_set(unsigned long long *p, unsigned long long n_slots)
 {
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof p);
+    const unsigned long long n = p ? n_slots : 0;
+    const hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(g_trace_slots), &n, sizeof n);
+    return e != hipSuccess ? e : hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof p);
 }
 #endif
 
