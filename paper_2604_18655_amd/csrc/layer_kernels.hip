@@ -1384,7 +1384,10 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         if (tile_ok) {
             // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
             // tile's 64 columns are fetched once and used by every block of 16 rows that holds
-            // such a row.  Four adapters are fetched per round trip.
+            // such a row.  Four passes are fetched per round trip: four adapters at ranks up to
+            // 32, else two adapters x two runs of 32 ranks, so that a round takes whole 128-byte
+            // pieces of the rows of B (the halves of a piece fetched in rounds far apart would
+            // cost the memory two accesses).
             const int n_lane = tile * TILE_N + l16;
             const int ad_row = lds.ad[lane];                // lane l looks after row l of the chunk
             const unsigned long long all = __ballot(ad_row >= 0);
@@ -1397,16 +1400,21 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                                                              (k_ok ? 32 * kk + 8 * lq : 0));
                 }
             };
-            for (int kk = 0; kk < r32 / 32; ++kk) {
-                const bool k_ok = 32 * kk + 8 * lq < P.rank;
+            const int nkk = r32 / 32;
+            for (int kk0 = 0; kk0 < nkk; kk0 += 2) {
+                const int nk = min(2, nkk - kk0);              // runs of 32 ranks per adapter and round
                 unsigned long long remaining = all;
                 int ordinal = 0;                               // of the adapter among those of the chunk
                 while (remaining) {
-                    // up to four adapters per round: their rows of B are requested together
                     int curs[4];
                     unsigned long long sames[4];
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
+                        if (nk == 2 && (b & 1)) {              // second run of ranks of the same adapter
+                            curs[b] = curs[b - 1];
+                            sames[b] = sames[b - 1];
+                            continue;
+                        }
                         // skip the adapters that other K units of this tile look after
                         while (remaining && ordinal % P.ksplit != ku) {
                             const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
@@ -1425,10 +1433,12 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                     }
                     u32x4 bf[4][4];
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) b_request(bf[b], curs[b], kk);
+                    for (int b = 0; b < 4; ++b) b_request(bf[b], curs[b], kk0 + (nk == 2 ? (b & 1) : 0));
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         if (!sames[b]) continue;
+                        const int kk = kk0 + (nk == 2 ? (b & 1) : 0);
+                        const bool k_ok = 32 * kk + 8 * lq < P.rank;
 #pragma unroll
                         for (int mb = 0; mb < 4; ++mb) {
                             if (!((sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
