@@ -1400,64 +1400,96 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                                                              (k_ok ? 32 * kk + 8 * lq : 0));
                 }
             };
+            // The rounds form a two-deep pipeline: the rows of B of the next round are on their
+            // way while the current round is computed.
+            struct Round {
+                int curs[4];
+                unsigned long long sames[4];
+                int kk0, nk;
+                bool any;
+            };
             const int nkk = r32 / 32;
-            for (int kk0 = 0; kk0 < nkk; kk0 += 2) {
-                const int nk = min(2, nkk - kk0);              // runs of 32 ranks per adapter and round
-                unsigned long long remaining = all;
-                int ordinal = 0;                               // of the adapter among those of the chunk
-                while (remaining) {
-                    int curs[4];
-                    unsigned long long sames[4];
+            int st_kk0 = 0, st_ordinal = 0;                    // where the enumeration stands
+            unsigned long long st_remaining = all;
+            // skip the adapters that other K units of this tile look after
+            auto skip_others = [&]() {
+                while (st_remaining && st_ordinal % P.ksplit != ku) {
+                    const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
+                    st_remaining &= ~__ballot(ad_row == other);
+                    ++st_ordinal;
+                }
+            };
+            auto next_round = [&](Round &r) {
+                skip_others();
+                while (!st_remaining && st_kk0 + 2 < nkk) {    // next pair of runs of 32 ranks
+                    st_kk0 += 2;
+                    st_remaining = all;
+                    st_ordinal = 0;
+                    skip_others();
+                }
+                r.any = st_remaining != 0;
+                r.kk0 = st_kk0;
+                r.nk = min(2, nkk - st_kk0);                   // runs of 32 ranks per adapter and round
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        if (nk == 2 && (b & 1)) {              // second run of ranks of the same adapter
-                            curs[b] = curs[b - 1];
-                            sames[b] = sames[b - 1];
-                            continue;
-                        }
-                        // skip the adapters that other K units of this tile look after
-                        while (remaining && ordinal % P.ksplit != ku) {
-                            const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
-                            remaining &= ~__ballot(ad_row == other);
-                            ++ordinal;
-                        }
-                        if (remaining) {
-                            curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(remaining));
-                            sames[b] = __ballot(ad_row == curs[b]);
-                            remaining &= ~sames[b];
-                            ++ordinal;
-                        } else {
-                            curs[b] = b ? curs[0] : 0;         // (a useless request that stays in bounds)
-                            sames[b] = 0;
-                        }
+                for (int b = 0; b < 4; ++b) {
+                    if (r.nk == 2 && (b & 1)) {                // second run of ranks of the same adapter
+                        r.curs[b] = r.curs[b - 1];
+                        r.sames[b] = r.sames[b - 1];
+                        continue;
                     }
-                    u32x4 bf[4][4];
+                    skip_others();
+                    if (st_remaining) {
+                        r.curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
+                        r.sames[b] = __ballot(ad_row == r.curs[b]);
+                        st_remaining &= ~r.sames[b];
+                        ++st_ordinal;
+                    } else {
+                        r.curs[b] = b ? r.curs[0] : 0;         // (a useless request that stays in bounds)
+                        r.sames[b] = 0;
+                    }
+                }
+            };
+            auto request = [&](u32x4 (&bf)[4][4], const Round &r) {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) b_request(bf[b], curs[b], kk0 + (nk == 2 ? (b & 1) : 0));
+                for (int b = 0; b < 4; ++b) b_request(bf[b], r.curs[b], r.kk0 + (r.nk == 2 ? (b & 1) : 0));
+            };
+            auto compute = [&](const u32x4 (&bf)[4][4], const Round &r) {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        if (!sames[b]) continue;
-                        const int kk = kk0 + (nk == 2 ? (b & 1) : 0);
-                        const bool k_ok = 32 * kk + 8 * lq < P.rank;
+                for (int b = 0; b < 4; ++b) {
+                    if (!r.sames[b]) continue;
+                    const int kk = r.kk0 + (r.nk == 2 ? (b & 1) : 0);
+                    const bool k_ok = 32 * kk + 8 * lq < P.rank;
 #pragma unroll
-                        for (int mb = 0; mb < 4; ++mb) {
-                            if (!((sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
-                            const bool mine = (sames[b] >> (16 * mb + l16)) & 1ull;
-                            float tv[8];
-                            const float *trow = tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq;
+                    for (int mb = 0; mb < 4; ++mb) {
+                        if (!((r.sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
+                        const bool mine = (r.sames[b] >> (16 * mb + l16)) & 1ull;
+                        float tv[8];
+                        const float *trow = tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq;
 #pragma unroll
-                            for (int i = 0; i < 8; ++i) tv[i] = mine ? trow[i] : 0.f;
-                            uint4 thi, tlo;
-                            split_bf16(tv, thi, tlo);
+                        for (int i = 0; i < 8; ++i) tv[i] = mine ? trow[i] : 0.f;
+                        uint4 thi, tlo;
+                        split_bf16(tv, thi, tlo);
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const uint4 b4 = k_ok ? __builtin_bit_cast(uint4, bf[b][j]) : make_uint4(0, 0, 0, 0);
-                                acc[mb][j] = mfma16(thi, b4, acc[mb][j]);
-                                acc[mb][j] = mfma16(tlo, b4, acc[mb][j]);
-                            }
+                        for (int j = 0; j < 4; ++j) {
+                            const uint4 b4 = k_ok ? __builtin_bit_cast(uint4, bf[b][j]) : make_uint4(0, 0, 0, 0);
+                            acc[mb][j] = mfma16(thi, b4, acc[mb][j]);
+                            acc[mb][j] = mfma16(tlo, b4, acc[mb][j]);
                         }
                     }
                 }
+            };
+            Round ra_, rb_;
+            u32x4 bfa[4][4], bfb[4][4];
+            next_round(ra_);
+            if (ra_.any) request(bfa, ra_);
+            while (ra_.any) {
+                next_round(rb_);
+                if (rb_.any) request(bfb, rb_);
+                compute(bfa, ra_);
+                if (!rb_.any) break;
+                next_round(ra_);
+                if (ra_.any) request(bfa, ra_);
+                compute(bfb, rb_);
             }
         }
     }
