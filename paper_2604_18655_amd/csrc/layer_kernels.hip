@@ -1161,6 +1161,9 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
     constexpr int GS = 4 / SPG;
     const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
     constexpr uint32_t CODE0 = 0x88888888u;                // eight codes 0 (offset binary 8), before placing the fields
+    // the fragments of x of a group stay in registers for the offset term and the products
+    // alike when the group is short (up to 2 k-steps); longer groups read them twice
+    constexpr bool KEEP_X = SPG <= 2;
 #pragma unroll
     for (int g = 0; g < GS; ++g) {
         const uint2 sv = r.sc[g];
@@ -1171,14 +1174,20 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
             const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
                            : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
             dead[j] = sj == 0.f;
-            const float unit = dead[j] ? (prev[j] == 0.f ? 1.f : prev[j]) : sj;
-            // (one rounding per change of unit: 2^-23 relative, a few dozen times over K)
+            const float unit = dead[j] ? prev[j] : sj;     // (prev starts at 1: never zero)
+            // (one rounding per group, 2^-23 relative; the reciprocal is good to one unit in
+            // the last place, which a few dozen groups over K do not turn into anything visible)
             ratio[j] = prev[j] * __builtin_amdgcn_rcpf(unit);
-
-            if (unit == prev[j]) ratio[j] = 1.f;
             prev[j] = unit;
         }
 
+        uint4 xk[KEEP_X ? SPG : 1][4];
+        if constexpr (KEEP_X) {
+#pragma unroll
+            for (int t = 0; t < SPG; ++t)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) xk[t][mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+        }
         // offset term of the group: -24 * sum of x over its inputs, per row
         f32x4 corr[4];
 #pragma unroll
@@ -1186,7 +1195,9 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
             corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < SPG; ++t) {
-                const uint4 xa = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+                uint4 xa;
+                if constexpr (KEEP_X) xa = xk[t][mb];
+                else xa = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
                 corr[mb] = mfma16(xa, neg24, corr[mb]);
             }
         }
@@ -1200,13 +1211,14 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
         for (int t = 0; t < SPG; ++t) {
             uint4 xa[4];
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-                xa[mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+            for (int mb = 0; mb < 4; ++mb) {
+                if constexpr (KEEP_X) xa[mb] = xk[t][mb];
+                else xa[mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+            }
             const u32x4 wv = r.w[g * SPG + t];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
-
                 // a dead column's codes become code 0 (the field layout is the same in every dword)
                 wj = dead[j] ? rotl32(CODE0, 3) : wj;
                 const uint4 wb = expand_codes(wj, mask, bias);
@@ -1289,7 +1301,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float prev[4] = {0.f, 0.f, 0.f, 0.f};
+    float prev[4] = {1.f, 1.f, 1.f, 1.f};                  // unit of acc per column block (acc = 0: any unit will do)
 
     WideRegs ra, rb;
     u32x4 xr[4];
