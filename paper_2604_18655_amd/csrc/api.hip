@@ -79,14 +79,6 @@ size_t partial_bytes(const mlora_w4_proj &p, int M, int launch_blocks)
     return (size_t)(ksplit_of(p, M, launch_blocks) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
 }
 
-// upper bound of the number of 16-row tiles the adapter segments of M rows can form
-int max_row_tiles(int M, int n_adapters)
-{
-    const int segs = n_adapters < M ? n_adapters : M;
-    const int bound = M / 16 + segs;
-    return bound < M ? bound : M;
-}
-
 }  // namespace
 
 extern "C" {
@@ -290,7 +282,9 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                 d.t_part = reinterpret_cast<float *>(ws);
                 ws += t_part_bytes(p, M);
                 // at most 16 rows: a shrink block per row; above: per 16-row tile of an adapter segment
-                d.n_shrink_blocks = (M <= 16 ? M : max_row_tiles(M, p.n_adapters)) * (d.r16 / 16) * d.kch;
+                d.n_shrink_blocks = (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS *
+                                                          shrink_tiles_per_chunk(M, p.n_adapters)) *
+                                    (d.r16 / 16) * d.kch;
                 shrink_blocks += d.n_shrink_blocks;
             } else {
                 d.n_adapters = 0;

@@ -13,6 +13,15 @@ struct GroupLds {
     int bad;                                      // an index was outside [-1, n_adapters)
 };
 
+// The same results for at most 64 rows (one wave's worth): at most 64 segments.
+struct GroupLds64 {
+    unsigned short perm[64];
+    unsigned short seg_adapter[64];
+    unsigned short seg_start[65];
+    int n_seg;
+    int bad;
+};
+
 // Rows without adapter (-1, or an out-of-range index) go to bucket n_adapters, which sorts last.
 __device__ inline int bucket_of(int a, int n_adapters, bool &bad)
 {
@@ -23,7 +32,8 @@ __device__ inline int bucket_of(int a, int n_adapters, bool &bad)
 // M <= 64: one wave, one row per lane, no LDS traffic until the results are written.  The
 // position of a row in the sorted order is (#rows in a smaller bucket) + (#earlier rows in the
 // same bucket); both sets are built as lane masks from one ballot per bit of the bucket id.
-__device__ inline void group_rows_wave(const int *row_adapter, int M, int n_adapters, GroupLds &g)
+template <class G>
+__device__ inline void group_rows_wave(const int *row_adapter, int M, int n_adapters, G &g)
 {
     const int lane = threadIdx.x & 63;
     const unsigned long long below = (1ull << lane) - 1ull;
@@ -129,6 +139,13 @@ __device__ inline void group_rows_counting(const int *row_adapter, int M, int n_
             }
         }
     }
+}
+
+// Called by all threads of a block, M <= 64.  On return g holds the permutation and the segments.
+__device__ inline void group_rows_lds64(const int *row_adapter, int M, int n_adapters, GroupLds64 &g)
+{
+    if ((threadIdx.x >> 6) == 0) group_rows_wave(row_adapter, M, n_adapters, g);
+    __syncthreads();
 }
 
 // Called by all threads of a block.  On return g holds the permutation and the segments.

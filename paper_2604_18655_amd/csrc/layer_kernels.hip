@@ -824,25 +824,31 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 struct ShrinkLds {
     static constexpr int SB = 4;                            // k-steps per batch
     static constexpr int ROW = SB * 64 + 16;                // bytes of a staged row; +16: rows 4 banks apart
-    GroupLds g;
-    float red[4][256];
-    unsigned char a[4][16 * ROW];
-    unsigned char x[4][16 * ROW];
+    GroupLds64 g;
+    alignas(16) float red[4][256];
+    alignas(16) unsigned char a[4][16 * ROW];              // (16-byte LDS accesses)
+    alignas(16) unsigned char x[4][16 * ROW];
 };
 
 __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int pi, int local, ShrinkLds &lds)
 {
     using L = ShrinkLds;
     constexpr int SB = L::SB;
-    GroupLds &g = lds.g;
+    GroupLds64 &g = lds.g;
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
     MLORA_TRACE_POINT(trace_slot, 0);
     const int jblocks = P.r16 / 16;
     const int kc = local % P.kch;
     const int jb = (local / P.kch) % jblocks;
-    const int ti = local / (P.kch * jblocks);
+    // the rows are handled in chunks of 64: row tile ti of chunk `chunk` (grouping 64 rows takes
+    // one wave a few ballots; a sort of all M rows in every block would cost more than the
+    // block's own work)
+    const int tpc = shrink_tiles_per_chunk(a.M, P.n_adapters);
+    const int ti_all = local / (P.kch * jblocks);
+    const int chunk = ti_all / tpc, ti = ti_all % tpc;
+    const int m_base = chunk * SHRINK_CHUNK_ROWS;
 
-    group_rows_lds(a.row_adapter, a.M, P.n_adapters, g);
+    group_rows_lds64(a.row_adapter + m_base, min(SHRINK_CHUNK_ROWS, a.M - m_base), P.n_adapters, g);
     MLORA_TRACE_POINT(trace_slot, 1);
 
     // locate row tile ti among the segments (16 rows per tile, tiles never straddle segments)
@@ -882,7 +888,7 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     for (int i = 0; i < 4; ++i) {
         const int rr = 4 * i + lq;                          // staged row: tile row of x, rank row of A
         x_ok[i] = rr < rows_here;
-        const int row = x_ok[i] ? (int)g.perm[first + rr] : 0;
+        const int row = m_base + (x_ok[i] ? (int)g.perm[first + rr] : 0);
         xsrc[i] = P.x + (size_t)row * P.K + (size_t)my_beg * KSTEP + l16 * 8;
         const int j = jb * 16 + rr;
         a_ok[i] = j < P.rank;
@@ -925,7 +931,7 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
         const float v = ((lds.red[0][e * 64 + lane] + lds.red[1][e * 64 + lane]) +
                          lds.red[2][e * 64 + lane]) + lds.red[3][e * 64 + lane];
         if (i < rows_here) {
-            const int m = g.perm[first + i];
+            const int m = m_base + g.perm[first + i];
             store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16, v);
         }
     }
