@@ -34,14 +34,19 @@ mlora_status check_proj(const mlora_w4_proj &p)
 }
 
 int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 16 * 16 : 0; }
-int kch_of(const mlora_w4_proj &p)
+// K chunks of the shrink step (at most MAX_KCHUNKS).  Decode shapes: 1024 inputs per chunk, split
+// over the four waves of a block (8 k-steps each, requested at once).  More than 16 rows: a wave
+// works through a chunk on its own for every row tile it is dealt; measured best with 512 inputs
+// per chunk below 64 rows (the finishing blocks need t early there) and 1024 from 64 rows on
+// (fewer partial sums for every finishing block to gather).
+int kch_of(const mlora_w4_proj &p, int M)
 {
-    int c = p.K / 1024;  // 1024 inputs per chunk (8 k-steps per wave, requested at once), at most MAX_KCHUNKS chunks
+    const int c = p.K / ((M > 16 && M < WIDE_MIN_ROWS) ? 512 : 1024);
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 size_t t_part_bytes(const mlora_w4_proj &p, int M)
 {
-    return round_up((size_t)kch_of(p) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
+    return round_up((size_t)kch_of(p, M) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
 }
 
 int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
@@ -278,12 +283,12 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                 d.n_adapters = p.n_adapters;
                 d.rank = p.rank;
                 d.r16 = r16_of(p);
-                d.kch = kch_of(p);
+                d.kch = kch_of(p, M);
                 d.t_part = reinterpret_cast<float *>(ws);
                 ws += t_part_bytes(p, M);
                 // at most 16 rows: a shrink block per row; above: per 16-row tile of an adapter segment
                 d.n_shrink_blocks = (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS *
-                                                          shrink_tiles_per_chunk(M, p.n_adapters)) *
+                                                          shrink_tile_shares(M, p.n_adapters)) *
                                     (d.r16 / 16) * d.kch;
                 shrink_blocks += d.n_shrink_blocks;
             } else {

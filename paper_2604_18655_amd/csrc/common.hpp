@@ -136,10 +136,12 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
 }
 
-// The grouped shrink step works on chunks of 64 rows: the rows of a chunk are grouped by adapter
-// (one wave, no sort) and every segment is cut into tiles of 16 rows.  Upper bound of the tiles of
-// a chunk of `rows` rows (at most 64): a tile per 16 rows plus one per segment, at most a tile
-// per row.  Host (grid size) and device (block index -> chunk, tile) use the same bound.
+// The grouped shrink step (more than 16 rows) works on chunks of 64 rows: the rows of a chunk are
+// grouped by adapter (one wave, no sort) and every segment is cut into tiles of 16 rows.  Upper
+// bound of the tiles of a chunk of `rows` rows (at most 64): a tile per 16 rows plus one per
+// segment, at most a tile per row.  A block's four waves work through up to 16 tiles; a chunk
+// that can have more is shared out over several blocks.  Host (grid size) and device (block
+// index -> chunk, share) use the same figures.
 constexpr int SHRINK_CHUNK_ROWS = 64;
 __host__ __device__ inline int max_row_tiles(int rows, int n_adapters)
 {
@@ -147,9 +149,9 @@ __host__ __device__ inline int max_row_tiles(int rows, int n_adapters)
     const int bound = rows / 16 + segs;
     return bound < rows ? bound : rows;
 }
-__host__ __device__ inline int shrink_tiles_per_chunk(int M, int n_adapters)
+__host__ __device__ inline int shrink_tile_shares(int M, int n_adapters)
 {
-    return max_row_tiles(M < SHRINK_CHUNK_ROWS ? M : SHRINK_CHUNK_ROWS, n_adapters);
+    return (max_row_tiles(M < SHRINK_CHUNK_ROWS ? M : SHRINK_CHUNK_ROWS, n_adapters) + 15) / 16;
 }
 
 // Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the

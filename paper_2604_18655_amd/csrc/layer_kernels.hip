@@ -821,12 +821,19 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 // memory channel and holds up every other wave of its compute unit.  So both are read in
 // contiguous runs (4 rows x 256 bytes per instruction) and turned into fragments through a
 // wave-private LDS buffer, four k-steps at a time.
+//
+// Grouped shrink (more than 16 rows per call).  A block = (chunk of 64 rows, share of the
+// chunk's row tiles, 16 ranks, chunk of K).  Wave 0 groups the chunk's rows by adapter (a few
+// ballots) and every segment is cut into tiles of 16 rows; the block's four waves then take the
+// tiles of the block's share in turn, each wave working through the whole K chunk of its tile on
+// its own: no reduction across waves, and few, long-lived blocks, which leaves the compute
+// units to the base blocks from the start of the launch (the blocks of a launch are placed in
+// grid order, so many short shrink blocks in front would hold every base block back).
 struct ShrinkLds {
     static constexpr int SB = 4;                            // k-steps per batch
     static constexpr int ROW = SB * 64 + 16;                // bytes of a staged row; +16: rows 4 banks apart
     GroupLds64 g;
-    alignas(16) float red[4][256];
-    alignas(16) unsigned char a[4][16 * ROW];              // (16-byte LDS accesses)
+    alignas(16) unsigned char a[4][16 * ROW];               // (16-byte LDS accesses)
     alignas(16) unsigned char x[4][16 * ROW];
 };
 
@@ -838,106 +845,102 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
     MLORA_TRACE_POINT(trace_slot, 0);
     const int jblocks = P.r16 / 16;
+    const int shares = shrink_tile_shares(a.M, P.n_adapters);
     const int kc = local % P.kch;
     const int jb = (local / P.kch) % jblocks;
-    // the rows are handled in chunks of 64: row tile ti of chunk `chunk` (grouping 64 rows takes
-    // one wave a few ballots; a sort of all M rows in every block would cost more than the
-    // block's own work)
-    const int tpc = shrink_tiles_per_chunk(a.M, P.n_adapters);
-    const int ti_all = local / (P.kch * jblocks);
-    const int chunk = ti_all / tpc, ti = ti_all % tpc;
+    const int share = (local / (P.kch * jblocks)) % shares;
+    const int chunk = local / (P.kch * jblocks * shares);
     const int m_base = chunk * SHRINK_CHUNK_ROWS;
 
     group_rows_lds64(a.row_adapter + m_base, min(SHRINK_CHUNK_ROWS, a.M - m_base), P.n_adapters, g);
     MLORA_TRACE_POINT(trace_slot, 1);
 
-    // locate row tile ti among the segments (16 rows per tile, tiles never straddle segments)
-    int seg = -1, first = 0, tiles_before = 0;
-    for (int s = 0; s < g.n_seg; ++s) {
-        const int len = (int)g.seg_start[s + 1] - (int)g.seg_start[s];
-        const int nt = (len + 15) / 16;
-        if (ti < tiles_before + nt) {
-            seg = s;
-            first = (int)g.seg_start[s] + 16 * (ti - tiles_before);
-            break;
-        }
-        tiles_before += nt;
-    }
-    if (seg < 0) {                                         // uniform over the block: nothing to do,
-        signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));       // but the finishing blocks count it
-        return;
-    }
-    const int adapter = g.seg_adapter[seg];
-    const int rows_here = min(16, (int)g.seg_start[seg + 1] - first);
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
-
-    // k-steps of this block, then of this wave (balanced splits)
+    // k-steps of this block's K chunk (balanced split)
     const int nks = P.K / KSTEP;
     const int q = nks / P.kch, r = nks % P.kch;
     const int blk_beg = kc * q + min(kc, r), blk_cnt = q + (kc < r ? 1 : 0);
-    const int wq_ = blk_cnt / 4, wr = blk_cnt % 4;
-    const int my_beg = blk_beg + wave * wq_ + min(wave, wr), my_cnt = wq_ + (wave < wr ? 1 : 0);
-
-    // loads: instruction i covers staged rows 4*i + lane/16, 16 bytes per lane (lane%16 of 16)
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    const uint16_t *xsrc[4], *asrc[4];
-    bool x_ok[4], a_ok[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rr = 4 * i + lq;                          // staged row: tile row of x, rank row of A
-        x_ok[i] = rr < rows_here;
-        const int row = m_base + (x_ok[i] ? (int)g.perm[first + rr] : 0);
-        xsrc[i] = P.x + (size_t)row * P.K + (size_t)my_beg * KSTEP + l16 * 8;
-        const int j = jb * 16 + rr;
-        a_ok[i] = j < P.rank;
-        asrc[i] = P.lora_a + ((size_t)adapter * P.rank + (a_ok[i] ? j : 0)) * P.K + (size_t)my_beg * KSTEP + l16 * 8;
-    }
     unsigned char *la = lds.a[wave], *lx = lds.x[wave];
-    u32x4 xv[4], av[4];
-    auto request = [&](int s0) {
-        const bool k_ok = (l16 >> 2) < my_cnt - s0;         // this lane's 8 inputs lie in k-step s0 + l16/4
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    // tiles of the chunk in segment order; tile t belongs to wave (t mod 4 * shares) - 4 * share
+    const int n_seg = g.n_seg;
+    int t = 0;
+    for (int sg = 0; sg < n_seg; ++sg) {
+        const int seg_first = (int)g.seg_start[sg], seg_len = (int)g.seg_start[sg + 1] - seg_first;
+        const int adapter = g.seg_adapter[sg];
+        for (int u = 0; u < seg_len; u += 16, ++t) {
+            if (t % (4 * shares) != 4 * share + wave) continue;
+            const int first = seg_first + u;
+            const int rows_here = min(16, seg_len - u);
+            // loads: instruction i covers staged rows 4*i + lane/16, 16 bytes per lane (lane%16 of 16)
+            const uint16_t *xsrc[4], *asrc[4];
+            bool x_ok[4], a_ok[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            xv[i] = (x_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)s0 * KSTEP) : zero;
-            av[i] = (a_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(asrc[i] + (size_t)s0 * KSTEP) : zero;
-        }
-    };
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (my_cnt > 0) request(0);
-    for (int s0 = 0; s0 < my_cnt; s0 += SB) {
+            for (int i = 0; i < 4; ++i) {
+                const int rr = 4 * i + lq;                  // staged row: tile row of x, rank row of A
+                x_ok[i] = rr < rows_here;
+                const int row = m_base + (x_ok[i] ? (int)g.perm[first + rr] : 0);
+                xsrc[i] = P.x + (size_t)row * P.K + (size_t)blk_beg * KSTEP + l16 * 8;
+                const int j = jb * 16 + rr;
+                a_ok[i] = j < P.rank;
+                asrc[i] = P.lora_a + ((size_t)adapter * P.rank + (a_ok[i] ? j : 0)) * P.K + (size_t)blk_beg * KSTEP + l16 * 8;
+            }
+            // four batches (a K chunk of 512 inputs, whole) in flight: the base blocks fill the
+            // memory queues at the same time, and a tile should cost one round trip, not four
+            constexpr int DEPTH = 2;
+            u32x4 xv[DEPTH][4], av[DEPTH][4];
+            auto request = [&](int set, int s0) {
+                const bool k_ok = (l16 >> 2) < blk_cnt - s0;    // this lane's 8 inputs lie in k-step s0 + l16/4
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<u32x4 *>(lx + (4 * i + lq) * L::ROW + l16 * 16) = xv[i];
-            *reinterpret_cast<u32x4 *>(la + (4 * i + lq) * L::ROW + l16 * 16) = av[i];
-        }
-        if (s0 + SB < my_cnt) request(s0 + SB);             // next batch on its way during the math
-        // (wave-private buffers: the wave's own LDS accesses are ordered, no barrier)
+                for (int i = 0; i < 4; ++i) {
+                    xv[set][i] = (x_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)s0 * KSTEP) : zero;
+                    av[set][i] = (a_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(asrc[i] + (size_t)s0 * KSTEP) : zero;
+                }
+            };
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            auto consume = [&](int set) {
+                // (wave-private buffers: the wave's own LDS accesses are ordered, no barrier)
 #pragma unroll
-        for (int s = 0; s < SB; ++s) {
-            const uint4 xa = *reinterpret_cast<const uint4 *>(lx + l16 * L::ROW + s * 64 + 16 * lq);
-            const uint4 ab = *reinterpret_cast<const uint4 *>(la + l16 * L::ROW + s * 64 + 16 * lq);
-            acc = mfma16(xa, ab, acc);
-        }
-    }
+                for (int i = 0; i < 4; ++i) {
+                    *reinterpret_cast<u32x4 *>(lx + (4 * i + lq) * L::ROW + l16 * 16) = xv[set][i];
+                    *reinterpret_cast<u32x4 *>(la + (4 * i + lq) * L::ROW + l16 * 16) = av[set][i];
+                }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) lds.red[wave][e * 64 + lane] = acc[e];
-    __syncthreads();
-    {
-        // thread (e, lane) owns tile row 4*(lane/16) + e and rank column lane%16
-        const int e = wave;
-        const int i = 4 * lq + e;
-        const float v = ((lds.red[0][e * 64 + lane] + lds.red[1][e * 64 + lane]) +
-                         lds.red[2][e * 64 + lane]) + lds.red[3][e * 64 + lane];
-        if (i < rows_here) {
-            const int m = m_base + g.perm[first + i];
-            store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16, v);
+                for (int s = 0; s < SB; ++s) {
+                    const uint4 xa = *reinterpret_cast<const uint4 *>(lx + l16 * L::ROW + s * 64 + 16 * lq);
+                    const uint4 ab = *reinterpret_cast<const uint4 *>(la + l16 * L::ROW + s * 64 + 16 * lq);
+                    acc = mfma16(xa, ab, acc);
+                }
+            };
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                if (d * SB < blk_cnt) request(d, d * SB);
+            for (int s0 = 0; s0 < blk_cnt; s0 += DEPTH * SB) {
+#pragma unroll
+                for (int d = 0; d < DEPTH; ++d) {
+                    if (s0 + d * SB < blk_cnt) {
+                        consume(d);
+                        if (s0 + (d + DEPTH) * SB < blk_cnt) request(d, s0 + (d + DEPTH) * SB);
+                    }
+                }
+            }
+            // lane (rank column l16, quarter lq) holds tile rows 4*lq + e
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * lq + e;
+                if (i < rows_here) {
+                    const int m = m_base + g.perm[first + i];
+                    store_shared(P.t_part + ((size_t)kc * a.M + m) * P.r16 + jb * 16 + l16, acc[e]);
+                }
+            }
         }
     }
     signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));
     MLORA_TRACE_POINT(trace_slot, 5);
 }
+
 
 // Decode shapes (at most 16 rows): one block per (row, block of 16 ranks, K chunk) and no
 // grouping.  The row's adapter index is one scalar load away, so the block's requests go out
