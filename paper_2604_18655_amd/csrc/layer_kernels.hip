@@ -1029,6 +1029,30 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
+// The same with the table chosen at run time.  Both tables are read whole (two wide scalar
+// loads from the kernel arguments) and the entries selected one by one: a pointer to the chosen
+// table would turn the search into 16 dependent scalar loads, each a round trip.
+__device__ __forceinline__ int find_proj(const int (&begin0)[MAX_PROJ_PER_LAUNCH], const int (&begin1)[MAX_PROJ_PER_LAUNCH],
+                                         bool second, int b, int &first)
+{
+    int t0[MAX_PROJ_PER_LAUNCH], t1[MAX_PROJ_PER_LAUNCH];
+#pragma unroll
+    for (int i = 0; i < MAX_PROJ_PER_LAUNCH; ++i) { t0[i] = begin0[i]; t1[i] = begin1[i]; }
+#pragma unroll
+    for (int i = 0; i < MAX_PROJ_PER_LAUNCH; i += 4)
+        asm volatile("" :: "s"(t0[i]), "s"(t0[i + 1]), "s"(t0[i + 2]), "s"(t0[i + 3]),
+                           "s"(t1[i]), "s"(t1[i + 1]), "s"(t1[i + 2]), "s"(t1[i + 3]));
+    int pi = 0;
+    first = second ? t1[0] : t0[0];
+#pragma unroll
+    for (int i = 1; i < MAX_PROJ_PER_LAUNCH; ++i) {
+        const int bi = second ? t1[i] : t0[i];
+        pi += (b >= bi) ? 1 : 0;
+        first = (b >= bi) ? bi : first;
+    }
+    return pi;
+}
+
 // ------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------
@@ -1062,6 +1086,14 @@ __device__ __forceinline__ ProjArgs fetch_proj(const LayerArgs &a, int pi)
     return P;
 }
 
+// The scalar fields at the end of the launch arguments, requested together at the kernel's start
+// (they share one cache line; left alone, the compiler loads each where it is first used).
+__device__ __forceinline__ void pin_launch_args(const LayerArgs &a)
+{
+    asm volatile("" :: "s"(a.row_adapter), "s"(a.M), "s"(a.y_fp32), "s"(a.m_pad), "s"(a.shrink_blocks),
+                       "s"(a.pre_base_blocks), "s"(a.ctrl), "s"(a.status), "s"(a.code_mask), "s"(a.code_bias));
+}
+
 // Entries past the last projection hold INT_MAX, so all 16 comparisons can be made without a
 // loop: the table arrives with one scalar load instead of one dependent load per projection.
 // first = begin[pi], picked from the same registers (begins are non-decreasing).
@@ -1084,6 +1116,7 @@ template <int MB, int XR>
 __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) void layer_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
+    pin_launch_args(a);
     const int b = (int)blockIdx.x;
     int first;
     if (b < a.shrink_blocks) {
@@ -1100,7 +1133,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     // once per launch is paid for by instruction fetch)
     const bool pre = b < a.shrink_blocks + a.pre_base_blocks;
     const int bb = b - a.shrink_blocks - (pre ? 0 : a.pre_base_blocks);
-    const int pi = pre ? find_proj(a.pre_begin, bb, first) : find_proj(a.main_begin, bb, first);
+    const int pi = find_proj(a.pre_begin, a.main_begin, !pre, bb, first);
     const ProjArgs P = fetch_proj(a, pi);
     const int local = bb - first;
     const int tiles = tiles_n(P.N);
@@ -1621,6 +1654,7 @@ template <int SPG>
 __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[wide_lds_bytes()];
+    pin_launch_args(a);
     const int b = (int)blockIdx.x;
     int first;
     if (b < a.shrink_blocks) {
