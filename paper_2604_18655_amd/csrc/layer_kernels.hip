@@ -1,16 +1,15 @@
 // The layer step: one launch.
 //
-// Base product.  A block of four waves owns one K unit (at most 2048 inputs) of one tile of 64
-// output columns for one chunk of 16*MB rows.  Each wave issues ALL loads of its share up
-// front (packed codes straight from HBM with one 128-bit load per lane and k-step, the rows of
-// x and the fp16 scales from L2), then turns every code dword into four bf16 pairs with 7
-// integer ops and feeds 16x16x32 bf16 MFMAs whose A operand is the block of rows of x.
-// Scales multiply the fp32 result of each scale group, so codes enter the matrix unit exactly.
-// The four partial tiles are added in LDS in a fixed order.
+// Base product.  A block of four waves owns one K unit of one tile of 64 output columns for one
+// chunk of rows (16, 32 or 64 of them: three kernels, below).  Packed codes come straight from
+// HBM with one 128-bit load per lane and k-step, the rows of x and the fp16 scales from L2;
+// every code dword becomes four bf16 pairs with 7 integer ops and feeds 16x16x32 bf16 MFMAs
+// whose A operand is a block of rows of x.  Scales multiply fp32 results, so the codes enter
+// the matrix unit exactly.  What several waves add up is added in a fixed order.
 //
-// Projections with more than 2048 inputs are cut into several K units per tile: units 1..
-// leave fp32 partial tiles in the workspace; unit 0 (the finishing block) adds them in order,
-// adds the LoRA term alpha * B[a(m)][n] . t[m] and stores y.
+// Long projections are cut into several K units per tile: units 1.. leave fp32 partial tiles in
+// the workspace; unit 0 (the finishing block) adds them in order, adds the LoRA term
+// alpha * B[a(m)][n] . t[m] and stores y.
 //
 // Order inside the launch.  The grid holds the shrink blocks first, then the split-K blocks,
 // then the finishing blocks.  A finishing block streams its weights without waiting for
@@ -19,10 +18,10 @@
 // completion.  Blocks are dispatched in index order, producers never wait, so every wait
 // ends; if one nevertheless runs out, the block sets the workspace status word and goes on.
 //
-// LoRA shrink.  A block owns one (16-row tile of an
-// adapter segment, block of 16 ranks, K chunk): after grouping the rows in LDS its four waves
-// split the chunk, each accumulating a 16x16 tile with MFMA (A operand: rows of x, B operand:
-// 16 rows of A[adapter]); the sum goes to t_part[chunk][row][rank].
+// LoRA shrink, t[m] = A[a(m)] . x[m] in K chunks, MFMA (A operand: rows of x, B operand: 16 rank
+// rows of A[adapter]); the partial sums go to t_part[chunk][row][rank].  Up to 16 rows: a block
+// per (row, 16 ranks, K chunk).  More rows: the rows of a chunk of 64 are grouped by adapter
+// and cut into tiles of 16, and a block's waves each take whole tiles.
 #include "group_rows.hpp"
 
 namespace mlora {
