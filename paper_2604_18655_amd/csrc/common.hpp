@@ -140,8 +140,11 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
 // grouped by adapter (one wave, no sort) and every segment is cut into tiles of 16 rows.  Upper
 // bound of the tiles of a chunk of `rows` rows (at most 64): a tile per 16 rows plus one per
 // segment, at most a tile per row.  A block's four waves work through up to 16 tiles; a chunk
-// that can have more is shared out over several blocks.  Host (grid size) and device (block
-// index -> chunk, share) use the same figures.
+// that can have more is shared out over several blocks.  Calls of 64 to 127 rows have a single
+// chunk and base blocks that are done early: there the finishing blocks wait for t, so a wave
+// gets at most one tile (measured: c5 68 -> 60 us; at 128 rows and more the extra, mostly idle
+// blocks cost more than they gain).  Host (grid size) and device (block index -> chunk, share)
+// use the same figures.
 constexpr int SHRINK_CHUNK_ROWS = 64;
 __host__ __device__ inline int max_row_tiles(int rows, int n_adapters)
 {
@@ -151,7 +154,8 @@ __host__ __device__ inline int max_row_tiles(int rows, int n_adapters)
 }
 __host__ __device__ inline int shrink_tile_shares(int M, int n_adapters)
 {
-    return (max_row_tiles(M < SHRINK_CHUNK_ROWS ? M : SHRINK_CHUNK_ROWS, n_adapters) + 15) / 16;
+    const int tiles = max_row_tiles(M < SHRINK_CHUNK_ROWS ? M : SHRINK_CHUNK_ROWS, n_adapters);
+    return (M >= SHRINK_CHUNK_ROWS && M < 2 * SHRINK_CHUNK_ROWS) ? (tiles + 3) / 4 : (tiles + 15) / 16;
 }
 
 // Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
