@@ -55,6 +55,30 @@ __device__ __forceinline__ float load_shared(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The same for 16 bytes at a time (the wide kernel's partial tiles: 64 KiB per block and unit).
+// There is no 128-bit atomic type, so these are the plain 128-bit instructions with the cache
+// policy of the 32-bit ones above (sc1), written out.  The compiler does not know that the load
+// is in flight: shared16_wait (vmcnt(0)) must stand between a batch of loads and the first use.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_shared16(float *p, f32x4_t v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ f32x4_t load_shared16(const float *p)
+{
+    f32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void shared16_wait(f32x4_t (&v)[16])
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                   "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                 :
+                 : "memory");
+}
+
 // all threads of the block, after their store_shared calls: wait until the own stores have been
 // acknowledged, meet, then count the block as done in `copies` counter lines
 __device__ __forceinline__ void signal_done(unsigned *counter, int copies)
@@ -1548,29 +1572,31 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     }
     MLORA_TRACE_POINT(trace_slot, 4);
     if (ku > 0) {
+        // A partial tile (64 rows x 64 columns) lies in the workspace in the order of the MFMA
+        // results, block (mb, j) of lane l at ((mb * 4 + j) * 64 + l) * 4: producer and consumer
+        // use the same mapping, and a lane moves 16 bytes per instruction.
         if (tile_ok) {
+            float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) store_shared(dst + 16 * j, acc[mb][j][e]);
-                }
+                for (int j = 0; j < 4; ++j) store_shared16(dst + (mb * 4 + j) * 256, acc[mb][j]);
             __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's stores have completed
             if (lane == 0) atomicAdd(pctr, 1u);
         }
     } else if (tile_ok && need_p) {
         if (!wait_count(pctr, (unsigned)(P.ksplit - 1)) && lane == 0) atomicOr(a.status, 1u);
-        for (int u = 0; u + 1 < P.ksplit; ++u)
+        for (int u = 0; u + 1 < P.ksplit; ++u) {
+            const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
+            f32x4_t pv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) pv[i] = load_shared16(src + i * 256);
+            shared16_wait(pv);
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0 + 16 * mb + 4 * lq + e) * TILE_N + l16;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[mb][j][e] += load_shared(src + 16 * j);
-                }
+                for (int j = 0; j < 4; ++j) acc[mb][j] += pv[mb * 4 + j];
+        }
     }
     MLORA_TRACE_POINT(trace_slot, 8);
     if (tile_ok && ku == 0) {
