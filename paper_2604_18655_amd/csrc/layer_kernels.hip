@@ -1421,35 +1421,42 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         __syncthreads();                                   // every wave is done with the x buffers
         float *tl = reinterpret_cast<float *>(lds.buf);
         const int r32 = (P.r16 + 31) / 32 * 32;            // ranks as the MFMAs see them (zero-filled)
-        // t = alpha * sum over the K chunks of the shrink partials, in fixed order; requested in
-        // batches of 4 entries x 4 chunks so that the round trips overlap
-
-        for (int i0 = 0; i0 < WIDE_ROWS * r32; i0 += 4 * 256) {
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
+        // t = alpha * sum over the K chunks of the shrink partials, in fixed order.  A thread takes
+        // four neighbouring ranks (16 bytes) at a time; requests go out in batches of 4 such
+        // quads x 4 chunks so that the round trips overlap.
+        const int qpr = r32 / 4;                           // quads per row of t
+        for (int i0 = 0; i0 < WIDE_ROWS * qpr; i0 += 4 * 256) {
+            f32x4_t v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             for (int kc0 = 0; kc0 < P.kch; kc0 += 4) {
-                float pv[4][4];
+                f32x4_t pv[16];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int idx = i0 + q * 256 + tid;
-                    const int ml = idx / r32, jj = idx % r32;
+                    const int ml = idx / qpr, jj = (idx % qpr) * 4;
                     const bool live = ml < rows_here && jj < P.r16;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const int kc = min(kc0 + c, P.kch - 1);
                         const float *src = live ? P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj : P.t_part;
-                        pv[q][c] = load_shared(src);
+                        pv[q * 4 + c] = load_shared16(src);
                     }
                 }
+                shared16_wait(pv);
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) v[q] += kc0 + c < P.kch ? pv[q][c] : 0.f;
+                    for (int c = 0; c < 4; ++c)
+                        if (kc0 + c < P.kch) v[q] += pv[q * 4 + c];
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int idx = i0 + q * 256 + tid;
-                const int ml = idx / r32, jj = idx % r32;
-                if (ml < WIDE_ROWS) tl[ml * L::T_STRIDE + jj] = (ml < rows_here && jj < P.r16) ? v[q] * P.alpha : 0.f;
+                const int ml = idx / qpr, jj = (idx % qpr) * 4;
+                const bool live = ml < rows_here && jj < P.r16;
+                if (ml < WIDE_ROWS)
+                    *reinterpret_cast<f32x4_t *>(tl + ml * L::T_STRIDE + jj) = live ? v[q] * P.alpha : f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
         if (tid < WIDE_ROWS) {
