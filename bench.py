@@ -164,7 +164,7 @@ def main():
     kern_ms = ev0.elapsed_time(ev1) / n_ev
     base_bytes = step_bytes / launches_per_step
     achieved = base_bytes / (kern_ms * 1e-3) / 1e9
-    wide = M >= 64                       # the library's kernel for 64 rows and more: bounded by the matrix units
+    wide = M >= 33                       # the library's kernel for 33 rows and more: bounded by the matrix units
     spg = w.projs[0].group // 32
     kernel_name = ("wide_kernel<%d>" % spg) if wide else \
         "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")

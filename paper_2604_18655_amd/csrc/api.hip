@@ -37,7 +37,7 @@ int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 1
 // K chunks of the shrink step (at most MAX_KCHUNKS).  Decode shapes: 1024 inputs per chunk, split
 // over the four waves of a block (8 k-steps each, requested at once).  More than 16 rows: a wave
 // works through a chunk on its own for every row tile it is dealt; measured best with 512 inputs
-// per chunk below 64 rows (the finishing blocks need t early there) and 1024 from 64 rows on
+// per chunk up to 32 rows (the finishing blocks need t early there) and 1024 in the wide kernel
 // (fewer partial sums for every finishing block to gather).
 int kch_of(const mlora_w4_proj &p, int M)
 {
@@ -52,7 +52,7 @@ size_t t_part_bytes(const mlora_w4_proj &p, int M)
 int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
 
 // K units per column tile.  Decode kernels: units of at most 2048 inputs (what a block stages of
-// x).  Wide kernel (64 rows and more): any unit length works, and a launch with few blocks is cut
+// x).  Wide kernel (33 rows and more): any unit length works, and a launch with few blocks is cut
 // further, down to 4 super-steps per unit, until it has about 256 of them; `launch_blocks` =
 // base blocks of the whole launch before that extra cut.
 int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
@@ -142,7 +142,7 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                              (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }
 
-// Projections of one launch: up to 16, and for the wide kernel (64 rows and more, compiled per
+// Projections of one launch: up to 16, and for the wide kernel (33 rows and more, compiled per
 // group size) only as long as the group size stays the same.
 static int launch_run(const mlora_w4_proj *projs, int n_left, int M)
 {
@@ -266,7 +266,7 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
             // finishing ones, or every K unit where the LoRA term is spread over them
             d.n_finish_blocks = tiles_n(p.N) * chunks * (M >= WIDE_MIN_ROWS ? d.ksplit : 1);
-            // base blocks: one per column tile, or per four of them for 64 rows and more
+            // base blocks: one per column tile, or per four of them in the wide kernel
             const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
             a.main_begin[i] = main_blocks;
             main_blocks += col_blocks;

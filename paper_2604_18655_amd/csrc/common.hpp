@@ -140,8 +140,8 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
 // grouped by adapter (one wave, no sort) and every segment is cut into tiles of 16 rows.  Upper
 // bound of the tiles of a chunk of `rows` rows (at most 64): a tile per 16 rows plus one per
 // segment, at most a tile per row.  A block's four waves work through up to 16 tiles; a chunk
-// that can have more is shared out over several blocks.  Calls of 64 to 127 rows have a single
-// chunk and base blocks that are done early: there the finishing blocks wait for t, so a wave
+// that can have more is shared out over several blocks.  Calls of 33 to 127 rows have at most two
+// chunks and base blocks that are done early: there the finishing blocks wait for t, so a wave
 // gets at most one tile (measured: c5 68 -> 60 us; at 128 rows and more the extra, mostly idle
 // blocks cost more than they gain).  Host (grid size) and device (block index -> chunk, share)
 // use the same figures.
@@ -155,7 +155,7 @@ __host__ __device__ inline int max_row_tiles(int rows, int n_adapters)
 __host__ __device__ inline int shrink_tile_shares(int M, int n_adapters)
 {
     const int tiles = max_row_tiles(M < SHRINK_CHUNK_ROWS ? M : SHRINK_CHUNK_ROWS, n_adapters);
-    return (M >= SHRINK_CHUNK_ROWS && M < 2 * SHRINK_CHUNK_ROWS) ? (tiles + 3) / 4 : (tiles + 15) / 16;
+    return (M > 32 && M < 2 * SHRINK_CHUNK_ROWS) ? (tiles + 3) / 4 : (tiles + 15) / 16;
 }
 
 // Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
@@ -185,7 +185,9 @@ hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s);
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
-constexpr int WIDE_MIN_ROWS = 64;      // calls with at least this many rows take the wide kernel
+// Calls with at least this many rows take the wide kernel (chunks of 64 rows): from 33 rows on
+// the 32-row kernel would stream the weights twice (measured: 54 -> 44 us for a c2-shaped layer).
+constexpr int WIDE_MIN_ROWS = 33;
 constexpr int WIDE_TILES_PER_BLOCK = 4;
 __host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : M < WIDE_MIN_ROWS ? 32 : 64; }
 // column tiles a base block covers

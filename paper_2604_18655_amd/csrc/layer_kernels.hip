@@ -1165,7 +1165,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
 }
 
 // ------------------------------------------------------------------------------------------
-// Wide shapes (64 rows or more per call): the product is a dense contraction and the matrix
+// Wide shapes (33 rows or more per call): the product is a dense contraction and the matrix
 // units are what bounds it.  A block covers 64 rows x 256 columns: its four waves share the rows
 // of x (staged in LDS, one super-step of 128 inputs at a time, double-buffered) and each wave
 // owns one 64-column tile, whose packed codes it streams into registers two super-steps ahead

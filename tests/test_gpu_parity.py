@@ -167,9 +167,12 @@ def test_config1_tiny(gpu):
     (256, 200, 64, 8, 3, 5),        # ragged N (not a multiple of 16), rank below one MFMA block
     (640, 72, 128, 24, 4, 16),      # K/128 = 5 super-steps over 4 waves, rank 24
     (384, 136, 32, 16, 5, 17),      # one row into the second block of 16
-    (1152, 96, 64, 64, 6, 33),      # two row chunks, rank 64
+    (1152, 96, 64, 64, 6, 33),      # first size of the 64-row kernel, rank 64
     (512, 64, 32, 128, 2, 9),       # maximum rank
-    (4096, 128, 128, 16, 9, 70),    # K chunks = 8 in the shrink step, three row chunks
+    (4096, 128, 128, 16, 9, 70),    # K chunks in the shrink step, two row chunks
+    (896, 136, 32, 24, 6, 24),      # 17-32 rows: one chunk of 32, 24 rows staged, odd super-steps
+    (2560, 200, 64, 16, 11, 32),    # 17-32 rows: full chunk, more adapters than a tile has rows
+    (768, 264, 128, 40, 4, 48),     # 33-63 rows: a partly empty chunk of 64
 ])
 def test_ragged_shapes(gpu, K, N, G, r, n_ad, M):
     prob = random_problem(K + N + M, K, N, G, r, n_ad)
@@ -187,7 +190,7 @@ def test_ragged_shapes(gpu, K, N, G, r, n_ad, M):
     (512, 1024, 32, 16, 40, 200),   # more adapters than rows of a 16-row block, four full blocks
 ])
 def test_wide_shapes(gpu, K, N, G, r, n_ad, M):
-    """64 rows and more take the kernel with 64 x 256 blocks: ragged tiles, chunks and ranks."""
+    """33 rows and more take the kernel with 64 x 256 blocks: ragged tiles, chunks and ranks."""
     prob = random_problem(K + N + M, K, N, G, r, n_ad)
     rng = np.random.default_rng(M)
     x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
@@ -288,7 +291,7 @@ def layer_on_gpu(gpu, probs, xs, rows, y_dtype):
 
 @pytest.mark.parametrize("M", [5, 40, 72])
 def test_layer_step_many_projections_mixed_groups(gpu, M):
-    """More projections than one launch holds (16), group sizes mixed (64 rows and more: a launch
+    """More projections than one launch holds (16), group sizes mixed (33 rows and more: a launch
     per run of equal group size), with and without split K, some without adapters."""
     lib, device, torch = gpu
     rng = np.random.default_rng(100 + M)

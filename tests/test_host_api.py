@@ -60,11 +60,13 @@ def test_workspace_bytes():
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == ctl + 256
     # K = 16384 = 8 units of 2048 inputs: 7 fp32 partial tiles [m_pad = 64][64] per tile of columns
     p = proj(K=16384, rank=64)
-    # (+ one counter line per (tile, row chunk) of a split-K projection: 1 tile x 1 chunk of 64
-    # rows; 2 chunks of 32 rows for 40 rows, padded to 64)
-    # (64 rows and more: a launch this small is cut further, here into 32 units of 4 x 128 inputs)
+    # (+ one counter line per (tile, row chunk) of a split-K projection: 1 tile x 1 chunk)
+    # (33 rows and more, chunks of 64 rows: a launch this small is cut further, here into 32
+    # units of 4 x 128 inputs; the shrink step leaves 16 chunks of partial sums)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == ctl + 1 * 128 + 16 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == ctl + 2 * 128 + 16 * 40 * 64 * 4 + 7 * 1 * 64 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == ctl + 1 * 128 + 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4
+    # (17 to 32 rows: one chunk of 32 rows, 8 units of 2048 inputs)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == ctl + 1 * 128 + 16 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4
     p = proj(K=4096, N=200, n_ad=0, rank=0, a=None, b=None)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == ctl + 4 * 128 + 1 * 4 * 16 * 64 * 4
     p = proj(n_ad=0, rank=0, a=None, b=None)
