@@ -51,18 +51,19 @@ size_t t_part_bytes(const mlora_w4_proj &p, int M)
 
 int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
 
-// K units per column tile.  Decode kernels: units of at most 2048 inputs (what a block stages of
-// x).  Wide kernel (33 rows and more): any unit length works, and a launch with few blocks is cut
-// further, down to 4 super-steps per unit, until it has about 256 of them; `launch_blocks` =
-// base blocks of the whole launch before that extra cut.
+// K units per column tile.  Decode kernels: units of at most 2048 inputs (16 super-steps: what a
+// block stages of x).  Wide kernel (33 rows and more): any unit length works.  A launch whose
+// base blocks with such units (`launch_blocks`) would leave most compute units idle gets shorter
+// units, the same length for all its projections: 8 super-steps below 160 blocks, 4 below 80
+// (measured on single projections and on whole layers of 64 rows: about 200 to 250 base
+// blocks, one per compute unit with the shrink blocks, beat both fewer and more).
 int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
 {
     const int nss = p.K / SUPER_K;
     int ks = (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
-    if (M >= WIDE_MIN_ROWS && launch_blocks > 0) {
-        const int factor = (256 + launch_blocks - 1) / launch_blocks;
-        const int most = nss / 4 > 1 ? nss / 4 : 1;
-        const int cut = ks * factor < most ? ks * factor : most;
+    if (M >= WIDE_MIN_ROWS && launch_blocks > 0 && launch_blocks < 160) {
+        const int unit = launch_blocks < 80 ? 4 : 8;
+        const int cut = (nss + unit / 2) / unit;
         if (cut > ks) ks = cut;
     }
     return ks;
