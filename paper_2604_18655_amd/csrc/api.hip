@@ -54,14 +54,17 @@ int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * r
 // K units per column tile.  Decode kernels: units of at most 2048 inputs (16 super-steps: what a
 // block stages of x).  Wide kernel (33 rows and more): any unit length works.  A launch whose
 // base blocks with such units (`launch_blocks`) would leave most compute units idle gets shorter
-// units, the same length for all its projections: 8 super-steps below 160 blocks, 4 below 80
-// (measured on single projections and on whole layers of 64 rows: about 200 to 250 base
-// blocks, one per compute unit with the shrink blocks, beat both fewer and more).
+// units, the same length for all its projections: 8 super-steps up to 240 blocks, 4 below 80.
+// Measured on single projections and on whole layers: up to 64 rows about 200 to 250 base
+// blocks (one per compute unit with the shrink blocks) beat both fewer and more; a layer of 128
+// rows (232 blocks) gains a quarter from 464 shorter ones, two per compute unit; from 256 rows on
+// (464 blocks and more) the long units win, and not splitting long projections at all is far
+// worse at any size (their blocks finish last).
 int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
 {
     const int nss = p.K / SUPER_K;
     int ks = (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
-    if (M >= WIDE_MIN_ROWS && launch_blocks > 0 && launch_blocks < 160) {
+    if (M >= WIDE_MIN_ROWS && launch_blocks > 0 && launch_blocks <= 240) {
         const int unit = launch_blocks < 80 ? 4 : 8;
         const int cut = (nss + unit / 2) / unit;
         if (cut > ks) ks = cut;
