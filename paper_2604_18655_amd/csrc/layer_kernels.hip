@@ -1548,9 +1548,14 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                         if (!((r.sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
                         const bool mine = (r.sames[b] >> (16 * mb + l16)) & 1ull;
                         float tv[8];
-                        const float *trow = tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq;
+                        // (16-byte aligned: rows of t are 528 bytes apart, a lane's run starts at a multiple of 32)
+                        const f32x4_t *trow = reinterpret_cast<const f32x4_t *>(tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq);
+                        const f32x4_t t0 = trow[0], t1 = trow[1];
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) tv[i] = mine ? trow[i] : 0.f;
+                        for (int i = 0; i < 4; ++i) {
+                            tv[i] = mine ? t0[i] : 0.f;
+                            tv[4 + i] = mine ? t1[i] : 0.f;
+                        }
                         uint4 thi, tlo;
                         split_bf16(tv, thi, tlo);
 #pragma unroll
