@@ -1195,7 +1195,6 @@ struct WideLds {
     static constexpr int BUF_BYTES = 2 * X_STAGE > T_BYTES ? 2 * X_STAGE : T_BYTES;
     alignas(16) unsigned char buf[BUF_BYTES];              // x stages; after the K loop: t
     alignas(16) float stage[WIDE_TILES][16 * (TILE_N + 4)]; // per wave: 16 rows of outputs on their way out
-    int ad[WIDE_ROWS];                                     // adapter of each row of the chunk (-1: none)
 };
 
 struct WideRegs {
@@ -1412,6 +1411,93 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[mb][j][e] *= prev[j];
 
+    // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
+    // tile's 64 columns are fetched once and used by every block of 16 rows that holds
+    // such a row.  Four passes are fetched per round trip: four adapters at ranks up to
+    // 32, else two adapters x two runs of 32 ranks, so that a round takes whole 128-byte
+    // pieces of the rows of B (the halves of a piece fetched in rounds far apart would
+    // cost the memory two accesses).
+    const int r32 = (P.r16 + 31) / 32 * 32;            // ranks as the MFMAs see them (zero-filled)
+    const int n_lane = tile * TILE_N + l16;
+    // lane l looks after row l of the chunk (a spare wave and a call without LoRA: no row)
+    int ad_row = -1;
+    if (lora && tile_ok && lane < rows_here) {
+        const int v = a.row_adapter[m0 + lane];
+        ad_row = (v >= 0 && v < P.n_adapters) ? v : -1;
+    }
+    const unsigned long long all = __ballot(ad_row >= 0);
+    auto b_request = [&](u32x4 (&bf)[4], int cur, int kk) {
+        const bool k_ok = 32 * kk + 8 * lq < P.rank;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = min(n_lane + 16 * j, N - 1);
+            bf[j] = *reinterpret_cast<const u32x4 *>(P.lora_b + ((size_t)cur * N + n) * P.rank +
+                                                     (k_ok ? 32 * kk + 8 * lq : 0));
+        }
+    };
+    // The rounds form a two-deep pipeline: the rows of B of the next round are on their
+    // way while the current round is computed.
+    struct Round {
+        int curs[4];
+        unsigned long long sames[4];
+        int kk0, nk;
+        bool any;
+    };
+    const int nkk = r32 / 32;
+    int st_kk0 = 0, st_ordinal = 0;                    // where the enumeration stands
+    unsigned long long st_remaining = all;
+    // skip the adapters that other K units of this tile look after
+    auto skip_others = [&]() {
+        while (st_remaining && st_ordinal % P.ksplit != ku) {
+            const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
+            st_remaining &= ~__ballot(ad_row == other);
+            ++st_ordinal;
+        }
+    };
+    auto next_round = [&](Round &r) {
+        skip_others();
+        while (!st_remaining && st_kk0 + 2 < nkk) {    // next pair of runs of 32 ranks
+            st_kk0 += 2;
+            st_remaining = all;
+            st_ordinal = 0;
+            skip_others();
+        }
+        r.any = st_remaining != 0;
+        r.kk0 = st_kk0;
+        r.nk = min(2, nkk - st_kk0);                   // runs of 32 ranks per adapter and round
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (r.nk == 2 && (b & 1)) {                // second run of ranks of the same adapter
+                r.curs[b] = r.curs[b - 1];
+                r.sames[b] = r.sames[b - 1];
+                continue;
+            }
+            skip_others();
+            if (st_remaining) {
+                r.curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
+                r.sames[b] = __ballot(ad_row == r.curs[b]);
+                st_remaining &= ~r.sames[b];
+                ++st_ordinal;
+            } else {
+                r.curs[b] = b ? r.curs[0] : 0;         // (a useless request that stays in bounds)
+                r.sames[b] = 0;
+            }
+        }
+    };
+    auto request = [&](u32x4 (&bf)[4][4], const Round &r) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) b_request(bf[b], r.curs[b], r.kk0 + (r.nk == 2 ? (b & 1) : 0));
+    };
+    // The first round's rows of B do not depend on t: they are requested before the wait for
+    // the shrink blocks and arrive while t is gathered.
+    Round ra_, rb_;
+    u32x4 bfa[4][4], bfb[4][4];
+    ra_.any = false;
+    if (lora && tile_ok) {
+        next_round(ra_);
+        if (ra_.any) request(bfa, ra_);
+    }
+
     // element (mb, j, e) of this lane: row 16*mb + 4*lq + e of the chunk, column 16*j + l16 of the tile
     if (tile_ok && need_s && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
     if (lora) {                                            // (uniform over the block)
@@ -1420,7 +1506,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         if (!tile_ok && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
         __syncthreads();                                   // every wave is done with the x buffers
         float *tl = reinterpret_cast<float *>(lds.buf);
-        const int r32 = (P.r16 + 31) / 32 * 32;            // ranks as the MFMAs see them (zero-filled)
         // t = alpha * sum over the K chunks of the shrink partials, in fixed order.  A thread takes
         // four neighbouring ranks (16 bytes) at a time; requests go out in batches of 4 such
         // quads x 4 chunks so that the round trips overlap.
@@ -1459,84 +1544,9 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                     *reinterpret_cast<f32x4_t *>(tl + ml * L::T_STRIDE + jj) = live ? v[q] * P.alpha : f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
-        if (tid < WIDE_ROWS) {
-            const int v = tid < rows_here ? a.row_adapter[m0 + tid] : -1;
-            lds.ad[tid] = (v >= 0 && v < P.n_adapters) ? v : -1;
-        }
         __syncthreads();
         MLORA_TRACE_POINT(trace_slot, 3);
         if (tile_ok) {
-            // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
-            // tile's 64 columns are fetched once and used by every block of 16 rows that holds
-            // such a row.  Four passes are fetched per round trip: four adapters at ranks up to
-            // 32, else two adapters x two runs of 32 ranks, so that a round takes whole 128-byte
-            // pieces of the rows of B (the halves of a piece fetched in rounds far apart would
-            // cost the memory two accesses).
-            const int n_lane = tile * TILE_N + l16;
-            const int ad_row = lds.ad[lane];                // lane l looks after row l of the chunk
-            const unsigned long long all = __ballot(ad_row >= 0);
-            auto b_request = [&](u32x4 (&bf)[4], int cur, int kk) {
-                const bool k_ok = 32 * kk + 8 * lq < P.rank;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n = min(n_lane + 16 * j, N - 1);
-                    bf[j] = *reinterpret_cast<const u32x4 *>(P.lora_b + ((size_t)cur * N + n) * P.rank +
-                                                             (k_ok ? 32 * kk + 8 * lq : 0));
-                }
-            };
-            // The rounds form a two-deep pipeline: the rows of B of the next round are on their
-            // way while the current round is computed.
-            struct Round {
-                int curs[4];
-                unsigned long long sames[4];
-                int kk0, nk;
-                bool any;
-            };
-            const int nkk = r32 / 32;
-            int st_kk0 = 0, st_ordinal = 0;                    // where the enumeration stands
-            unsigned long long st_remaining = all;
-            // skip the adapters that other K units of this tile look after
-            auto skip_others = [&]() {
-                while (st_remaining && st_ordinal % P.ksplit != ku) {
-                    const int other = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
-                    st_remaining &= ~__ballot(ad_row == other);
-                    ++st_ordinal;
-                }
-            };
-            auto next_round = [&](Round &r) {
-                skip_others();
-                while (!st_remaining && st_kk0 + 2 < nkk) {    // next pair of runs of 32 ranks
-                    st_kk0 += 2;
-                    st_remaining = all;
-                    st_ordinal = 0;
-                    skip_others();
-                }
-                r.any = st_remaining != 0;
-                r.kk0 = st_kk0;
-                r.nk = min(2, nkk - st_kk0);                   // runs of 32 ranks per adapter and round
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    if (r.nk == 2 && (b & 1)) {                // second run of ranks of the same adapter
-                        r.curs[b] = r.curs[b - 1];
-                        r.sames[b] = r.sames[b - 1];
-                        continue;
-                    }
-                    skip_others();
-                    if (st_remaining) {
-                        r.curs[b] = __builtin_amdgcn_readlane(ad_row, (int)__builtin_ctzll(st_remaining));
-                        r.sames[b] = __ballot(ad_row == r.curs[b]);
-                        st_remaining &= ~r.sames[b];
-                        ++st_ordinal;
-                    } else {
-                        r.curs[b] = b ? r.curs[0] : 0;         // (a useless request that stays in bounds)
-                        r.sames[b] = 0;
-                    }
-                }
-            };
-            auto request = [&](u32x4 (&bf)[4][4], const Round &r) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) b_request(bf[b], r.curs[b], r.kk0 + (r.nk == 2 ? (b & 1) : 0));
-            };
             auto compute = [&](const u32x4 (&bf)[4][4], const Round &r) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
@@ -1567,10 +1577,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                     }
                 }
             };
-            Round ra_, rb_;
-            u32x4 bfa[4][4], bfb[4][4];
-            next_round(ra_);
-            if (ra_.any) request(bfa, ra_);
             while (ra_.any) {
                 next_round(rb_);
                 if (rb_.any) request(bfb, rb_);
