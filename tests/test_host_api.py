@@ -67,6 +67,11 @@ def test_workspace_bytes():
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == ctl + 1 * 128 + 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4
     # (17 to 32 rows: one chunk of 32 rows, 8 units of 2048 inputs)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == ctl + 1 * 128 + 16 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4
+    # a launch of the 64-row kernel with 80 to 240 base blocks gets K units of 8 x 128 inputs:
+    # K = 3072, N = 8192 (128 tiles = 32 blocks of columns), 128 rows (2 chunks) -> 3 units
+    p = proj(K=3072, N=8192, group=64, rank=16)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 128) == (ctl + 128 * 2 * 128 + 3 * 128 * 16 * 4
+                                                                + 2 * 128 * 128 * 64 * 4)
     p = proj(K=4096, N=200, n_ad=0, rank=0, a=None, b=None)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == ctl + 4 * 128 + 1 * 4 * 16 * 64 * 4
     p = proj(n_ad=0, rank=0, a=None, b=None)
