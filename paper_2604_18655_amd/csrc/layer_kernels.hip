@@ -458,6 +458,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     int l16 = lane & 15, lq = lane >> 4;
     [[maybe_unused]] const int trace_slot = (int)blockIdx.x * WAVES + wave;
     MLORA_TRACE_POINT(trace_slot, 0);
+    // the units of a split projection form the longest chain of the launch: they go first
+    // wherever they share a SIMD with other waves
+    if (P.ksplit > 1) __builtin_amdgcn_s_setprio(2);
 
     // super-steps of this K unit, then of this wave (balanced splits)
     const int nss = K / SUPER_K;
