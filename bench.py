@@ -37,8 +37,8 @@ MEASURED_TRAFFIC = {"c2": 49004947}     # bytes per launch: profiles/layer_kerne
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c2", help="c2 (default), c1, c3, c4_decode, c4_prefill, c5_up, c5_down")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
