@@ -1055,30 +1055,6 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
-// The same with the table chosen at run time.  Both tables are read whole (two wide scalar
-// loads from the kernel arguments) and the entries selected one by one: a pointer to the chosen
-// table would turn the search into 16 dependent scalar loads, each a round trip.
-__device__ __forceinline__ int find_proj(const int (&begin0)[MAX_PROJ_PER_LAUNCH], const int (&begin1)[MAX_PROJ_PER_LAUNCH],
-                                         bool second, int b, int &first)
-{
-    int t0[MAX_PROJ_PER_LAUNCH], t1[MAX_PROJ_PER_LAUNCH];
-#pragma unroll
-    for (int i = 0; i < MAX_PROJ_PER_LAUNCH; ++i) { t0[i] = begin0[i]; t1[i] = begin1[i]; }
-#pragma unroll
-    for (int i = 0; i < MAX_PROJ_PER_LAUNCH; i += 4)
-        asm volatile("" :: "s"(t0[i]), "s"(t0[i + 1]), "s"(t0[i + 2]), "s"(t0[i + 3]),
-                           "s"(t1[i]), "s"(t1[i + 1]), "s"(t1[i + 2]), "s"(t1[i + 3]));
-    int pi = 0;
-    first = second ? t1[0] : t0[0];
-#pragma unroll
-    for (int i = 1; i < MAX_PROJ_PER_LAUNCH; ++i) {
-        const int bi = second ? t1[i] : t0[i];
-        pi += (b >= bi) ? 1 : 0;
-        first = (b >= bi) ? bi : first;
-    }
-    return pi;
-}
-
 // ------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------
@@ -1112,18 +1088,32 @@ __device__ __forceinline__ ProjArgs fetch_proj(const LayerArgs &a, int pi)
     return P;
 }
 
-// The scalar fields at the end of the launch arguments, requested together at the kernel's start
-// (they share one cache line; left alone, the compiler loads each where it is first used).
-__device__ __forceinline__ void pin_launch_args(const LayerArgs &a)
+// The three block tables and the scalar fields at the end of the launch arguments, all requested
+// together at the kernel's start: one scalar round trip (the cache behind the kernel arguments
+// is cold at every launch) instead of one for the scalars, a dependent one for the table of the
+// block's kind and then the projection's record.  Left alone, the compiler loads each value
+// where it is first used; and a pointer to the table of the block's kind would turn the search
+// below into 16 dependent loads.
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+static_assert(MAX_PROJ_PER_LAUNCH == 16, "the block tables are read as vectors of 16");
+struct LaunchTables {
+    i32x16 shrink, pre, main;
+};
+__device__ __forceinline__ LaunchTables pin_launch_args(const LayerArgs &a)
 {
-    asm volatile("" :: "s"(a.row_adapter), "s"(a.M), "s"(a.y_fp32), "s"(a.m_pad), "s"(a.shrink_blocks),
-                       "s"(a.pre_base_blocks), "s"(a.ctrl), "s"(a.status), "s"(a.code_mask), "s"(a.code_bias));
+    LaunchTables t;
+    t.shrink = *reinterpret_cast<const i32x16 *>(a.shrink_begin);
+    t.pre = *reinterpret_cast<const i32x16 *>(a.pre_begin);
+    t.main = *reinterpret_cast<const i32x16 *>(a.main_begin);
+    asm volatile("" :: "s"(t.shrink), "s"(t.pre), "s"(t.main), "s"(a.row_adapter), "s"(a.M), "s"(a.y_fp32),
+                       "s"(a.m_pad), "s"(a.shrink_blocks), "s"(a.pre_base_blocks), "s"(a.ctrl), "s"(a.status),
+                       "s"(a.code_mask), "s"(a.code_bias));
+    return t;
 }
 
 // Entries past the last projection hold INT_MAX, so all 16 comparisons can be made without a
-// loop: the table arrives with one scalar load instead of one dependent load per projection.
-// first = begin[pi], picked from the same registers (begins are non-decreasing).
-__device__ __forceinline__ int find_proj(const int (&begin)[MAX_PROJ_PER_LAUNCH], int b, int &first)
+// loop.  first = begin[pi], picked from the same registers (begins are non-decreasing).
+__device__ __forceinline__ int find_proj(const i32x16 &begin, int b, int &first)
 {
     int pi = 0;
     first = begin[0];
@@ -1142,12 +1132,12 @@ template <int MB, int XR>
 __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) void layer_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
-    pin_launch_args(a);
+    const LaunchTables tables = pin_launch_args(a);
     const int b = (int)blockIdx.x;
     int first;
     if (b < a.shrink_blocks) {
         if (blockIdx.y != 0) return;
-        const int pi = find_proj(a.shrink_begin, b, first);
+        const int pi = find_proj(tables.shrink, b, first);
         // (the instances with one block of 16 rows are the ones launched for M <= 16)
         if constexpr (MB == 1) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
         else                   shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
@@ -1159,7 +1149,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     // once per launch is paid for by instruction fetch)
     const bool pre = b < a.shrink_blocks + a.pre_base_blocks;
     const int bb = b - a.shrink_blocks - (pre ? 0 : a.pre_base_blocks);
-    const int pi = find_proj(a.pre_begin, a.main_begin, !pre, bb, first);
+    const int pi = find_proj(pre ? tables.pre : tables.main, bb, first);
     const ProjArgs P = fetch_proj(a, pi);
     const int local = bb - first;
     const int tiles = tiles_n(P.N);
@@ -1700,12 +1690,12 @@ template <int SPG>
 __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[wide_lds_bytes()];
-    pin_launch_args(a);
+    const LaunchTables tables = pin_launch_args(a);
     const int b = (int)blockIdx.x;
     int first;
     if (b < a.shrink_blocks) {
         if (blockIdx.y != 0) return;
-        const int pi = find_proj(a.shrink_begin, b, first);
+        const int pi = find_proj(tables.shrink, b, first);
         shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
@@ -1713,14 +1703,14 @@ __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
     const int m0 = (int)blockIdx.y * WIDE_ROWS;
     if (b < a.shrink_blocks + a.pre_base_blocks) {
         const int pb = b - a.shrink_blocks;
-        const int pi = find_proj(a.pre_begin, pb, first);
+        const int pi = find_proj(tables.pre, pb, first);
         const ProjArgs P = fetch_proj(a, pi);
         const int local = pb - first;
         const int groups = (tiles_n(P.N) + WIDE_TILES - 1) / WIDE_TILES;
         wide_unit<SPG>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
     } else {
         const int mb_ = b - a.shrink_blocks - a.pre_base_blocks;
-        const int pi = find_proj(a.main_begin, mb_, first);
+        const int pi = find_proj(tables.main, mb_, first);
         const ProjArgs P = fetch_proj(a, pi);
         wide_unit<SPG>(a, P, pi, mb_ - first, 0, m0, lds);
     }
