@@ -270,6 +270,12 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
             // finishing ones, or every K unit where the LoRA term is spread over them
             d.n_finish_blocks = tiles_n(p.N) * chunks * (M >= WIDE_MIN_ROWS ? d.ksplit : 1);
+            d.unit_q = (p.K / SUPER_K) / d.ksplit;
+            d.unit_r = (p.K / SUPER_K) % d.ksplit;
+            d.spg_shift = d.spg == 4 ? 2 : d.spg == 2 ? 1 : 0;
+            d.ctr_copies = 1;
+            while (d.ctr_copies * 2 <= CTR_REPL && d.ctr_copies * 2 <= d.n_finish_blocks) d.ctr_copies *= 2;
+            d.tiles_inv = (unsigned)((0x100000000ull + (unsigned)tiles_n(p.N) - 1) / (unsigned)tiles_n(p.N));
             // base blocks: one per column tile, or per four of them in the wide kernel
             const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
             a.main_begin[i] = main_blocks;

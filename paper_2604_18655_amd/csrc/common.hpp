@@ -76,6 +76,14 @@ struct ProjArgs {
     int n_shrink_blocks;       // shrink blocks of this projection (each bumps its counter once)
     int n_finish_blocks;       // finishing blocks of this projection (tiles x row chunks)
     int part_ctr;              // index of this projection's first split-K counter line in ctrl
+    // Derived on the host so that no block starts with integer divisions (each one costs some 30
+    // cold instructions, and they sat in front of the first memory request of every block):
+    int unit_q, unit_r;        // (K / 128) / ksplit and (K / 128) % ksplit: super-steps per K unit
+    int spg_shift;             // log2(spg)
+    int ctr_copies;            // copies of the shrink counter in use: a power of two, at most
+                               // min(CTR_REPL, n_finish_blocks)
+    unsigned tiles_inv;        // ceil(2^32 / tiles) for tiles > 1: block index / tiles = umulhi(index,
+                               // tiles_inv), exact while index * tiles < 2^32
 };
 
 // Counters in the workspace that order the blocks of one launch (all zero between calls).

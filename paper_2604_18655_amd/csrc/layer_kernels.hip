@@ -464,7 +464,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 
     // super-steps of this K unit, then of this wave (balanced splits)
     const int nss = K / SUPER_K;
-    const int uq = nss / P.ksplit, ur = nss % P.ksplit;
+    const int uq = P.unit_q, ur = P.unit_r;
     const int unit_beg = ku * uq + min(ku, ur), unit_cnt = uq + (ku < ur ? 1 : 0);
     const int q = unit_cnt / WAVES, r = unit_cnt % WAVES;
     const int my_cnt = q + (wave < r ? 1 : 0);
@@ -472,7 +472,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const int my_beg = my_cnt > 0 ? unit_beg + wave * q + min(wave, r) : unit_beg;
 
     const int ksteps = K / KSTEP;
-    const int ngroups = ksteps / P.spg;
+    const int ngroups = ksteps >> P.spg_shift;
     const uint4 *codes_tile = P.codes + (size_t)tile * ksteps * 64;
     const uint2 *scales_tile = P.scales + (size_t)tile * ngroups * 16;
 
@@ -568,8 +568,8 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const int tiles = tiles_n(N);
     const int chunk = m0 / ROWS, chunks = a.m_pad / ROWS;
     const int fin = tile * chunks + chunk;                 // this finishing block among its projection's
-    const int copies = min(CTR_REPL, P.n_finish_blocks);   // copies of the shrink counter in use
-    unsigned *const sctr = a.ctrl + shrink_ctr(pi, fin % copies);
+    const int copies = P.ctr_copies;                       // copies of the shrink counter in use (a power of two)
+    unsigned *const sctr = a.ctrl + shrink_ctr(pi, fin & (copies - 1));
     unsigned *const pctr = a.ctrl + P.part_ctr + fin * CTR_STRIDE;
     const bool need_s = lora, need_p = ku == 0 && P.ksplit > 1;
     unsigned seen_s = 0, seen_p = 0;                       // what an early look at them showed
@@ -589,12 +589,12 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) ad_raw[mb] = ra_safe[min(m0 + elem_ml(4 * mb), ra_last)];
         const u32x4 *wp = reinterpret_cast<const u32x4 *>(codes_tile) + (size_t)ks_first * 64;
-        const uint2 *sp = scales_tile + (size_t)(ks_first / P.spg) * 16;
+        const uint2 *sp = scales_tile + (size_t)(ks_first >> P.spg_shift) * 16;
         const unsigned char *xl = buf + min(l16, rows_x - 1) * L::XROW + 16 * lq;
         StreamRegs sa, sb;
         // an idle wave requests (and ignores) the unit's first super-step
-        stream_request(sa, wp, sp, 0, max(my_cnt, 1), 4 / P.spg, lane);
-        stream_request(sb, wp, sp, 1, my_cnt, 4 / P.spg, lane);
+        stream_request(sa, wp, sp, 0, max(my_cnt, 1), 4 >> P.spg_shift, lane);
+        stream_request(sb, wp, sp, 1, my_cnt, 4 >> P.spg_shift, lane);
         __builtin_amdgcn_sched_barrier(0);                     // (the requests stay ahead of the wait for x)
 #pragma unroll
         for (int i = 0; i < XR; ++i) *reinterpret_cast<u32x4 *>(buf + lane * 16 + i * L::XROW) = xr[i];
@@ -830,7 +830,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     // passed it (the barrier above), a copy of the shrink counter by the last block that used it.
     if (tid == 0 && need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0 && need_s) {
-        const int users = P.n_finish_blocks / copies + (fin % copies < P.n_finish_blocks % copies ? 1 : 0);
+        const int users = P.n_finish_blocks / copies + ((fin & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
         if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
             __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -963,7 +963,7 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
             }
         }
     }
-    signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));
+    signal_done(a.ctrl + shrink_ctr(pi, 0), P.ctr_copies);
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
@@ -1051,7 +1051,7 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
         }
     }
     // (a base-only row has nothing to write, but the finishing blocks count its blocks all the same)
-    signal_done(a.ctrl + shrink_ctr(pi, 0), min(CTR_REPL, P.n_finish_blocks));
+    signal_done(a.ctrl + shrink_ctr(pi, 0), P.ctr_copies);
     MLORA_TRACE_POINT(trace_slot, 5);
 }
 
@@ -1085,6 +1085,7 @@ __device__ __forceinline__ ProjArgs fetch_proj(const LayerArgs &a, int pi)
                  "s"(P.t_part), "s"(P.partial));
     asm volatile("" :: "s"(P.K), "s"(P.N), "s"(P.spg), "s"(P.n_adapters), "s"(P.rank), "s"(P.r16),
                  "s"(P.kch), "s"(P.alpha), "s"(P.ksplit));
+    asm volatile("" :: "s"(P.unit_q), "s"(P.unit_r), "s"(P.spg_shift), "s"(P.ctr_copies), "s"(P.tiles_inv));
     return P;
 }
 
@@ -1153,8 +1154,9 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     const ProjArgs P = fetch_proj(a, pi);
     const int local = bb - first;
     const int tiles = tiles_n(P.N);
-    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, pre ? local % tiles : local,
-                                                      pre ? 1 + local / tiles : 0, m0, lds);
+    // local / tiles (tiles_inv = ceil(2^32 / tiles) does not fit 32 bits for a single tile)
+    const int unit = !pre ? 0 : tiles == 1 ? local : (int)__umulhi((unsigned)local, P.tiles_inv);
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, local - unit * tiles, pre ? 1 + unit : 0, m0, lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1315,7 +1317,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     const int tile = tile_ok ? tile_raw : 0;
 
     const int nss = K / SUPER_K;
-    const int uq = nss / P.ksplit, ur = nss % P.ksplit;
+    const int uq = P.unit_q, ur = P.unit_r;
     const int unit_beg = ku * uq + min(ku, ur), unit_cnt = uq + (ku < ur ? 1 : 0);
     const int ksteps = K / KSTEP;
     constexpr int gs = 4 / SPG;
@@ -1333,8 +1335,8 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     const int chunk = m0 / WIDE_ROWS, chunks = a.m_pad / WIDE_ROWS;
     const int fin = tile * chunks + chunk;
     const int user = fin * P.ksplit + ku;
-    const int copies = min(CTR_REPL, P.n_finish_blocks);
-    unsigned *const sctr = a.ctrl + shrink_ctr(pi, user % copies);
+    const int copies = P.ctr_copies;
+    unsigned *const sctr = a.ctrl + shrink_ctr(pi, user & (copies - 1));
     unsigned *const pctr = a.ctrl + P.part_ctr + fin * CTR_STRIDE;
     const bool need_s = lora, need_p = ku == 0 && P.ksplit > 1;
 
@@ -1672,7 +1674,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     if (tile_ok && lane == 0) {
         if (need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (need_s) {
-            const int users = P.n_finish_blocks / copies + (user % copies < P.n_finish_blocks % copies ? 1 : 0);
+            const int users = P.n_finish_blocks / copies + ((user & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
             if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
                 __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
