@@ -93,7 +93,7 @@ __device__ __forceinline__ bool wait_count(unsigned *counter, unsigned expected)
 {
     for (int i = 0; i < SPIN_LIMIT; ++i) {
         if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) return true;
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(1);
     }
     return false;
 }
@@ -830,7 +830,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     // passed it (the barrier above), a copy of the shrink counter by the last block that used it.
     if (tid == 0 && need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0 && need_s) {
-        const int users = P.n_finish_blocks / copies + ((fin & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
+        const int users = (P.n_finish_blocks >> (31 - __clz(copies))) + ((fin & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
         if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
             __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1674,7 +1674,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     if (tile_ok && lane == 0) {
         if (need_p) __hip_atomic_store(pctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (need_s) {
-            const int users = P.n_finish_blocks / copies + ((user & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
+            const int users = (P.n_finish_blocks >> (31 - __clz(copies))) + ((user & (copies - 1)) < (P.n_finish_blocks & (copies - 1)) ? 1 : 0);
             if (atomicAdd(sctr + 1, 1u) + 1u == (unsigned)users) {
                 __hip_atomic_store(sctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
