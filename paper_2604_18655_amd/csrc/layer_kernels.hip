@@ -685,7 +685,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     f32x4{acc[mb][0][e], acc[mb][1][e], acc[mb][2][e], acc[mb][3][e]};
     }
 
-    constexpr int PU = 3;
+    constexpr int PU = MB == 1 ? 7 : 3;                   // split-K units (beside the block's own) the short way out adds
     // The common decode case gets a short, nearly branch-free way out (code that runs once per
     // launch is paid for by the instruction fetch, so its length is its cost): a finishing block
     // whose LoRA term, if any, was prefetched above and whose K has at most PU + 1 units.
@@ -701,7 +701,22 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     const int m = min(m0 + elem_ml(qq), M - 1);
                     const float *src = P.partial + ((size_t)tile * a.m_pad + m) * TILE_N + elem_col(qq);
 #pragma unroll
-                    for (int u = 0; u < PU; ++u) pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride);
+                    for (int u = 0; u < 3; ++u) pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride);
+                }
+                // (more than four units: K above 8192; the common case does not pay for these loads)
+                if (PU > 3 && P.ksplit > 4) {
+#pragma unroll
+                    for (int qq = 0; qq < EPT; ++qq) {
+                        const int m = min(m0 + elem_ml(qq), M - 1);
+                        const float *src = P.partial + ((size_t)tile * a.m_pad + m) * TILE_N + elem_col(qq);
+#pragma unroll
+                        for (int u = 3; u < PU; ++u) pv[qq][u] = load_shared(src + (size_t)min(u, P.ksplit - 2) * ustride);
+                    }
+                } else {
+#pragma unroll
+                    for (int qq = 0; qq < EPT; ++qq)
+#pragma unroll
+                        for (int u = 3; u < PU; ++u) pv[qq][u] = 0.f;
                 }
             }
             MLORA_TRACE_POINT(trace_slot, 3);

@@ -173,6 +173,9 @@ def test_config1_tiny(gpu):
     (896, 136, 32, 24, 6, 24),      # 17-32 rows: one chunk of 32, 24 rows staged, odd super-steps
     (2560, 200, 64, 16, 11, 32),    # 17-32 rows: full chunk, more adapters than a tile has rows
     (768, 264, 128, 40, 4, 48),     # 33-63 rows: a partly empty chunk of 64
+    (12288, 136, 32, 16, 3, 7),     # decode with 6 K units (more than the 4 of the common case)
+    (16384, 72, 64, 8, 2, 12),      # decode with 8 K units, 9-16 rows
+    (20480, 64, 128, 16, 2, 5),     # decode with 10 K units: the general way out
 ])
 def test_ragged_shapes(gpu, K, N, G, r, n_ad, M):
     prob = random_problem(K + N + M, K, N, G, r, n_ad)
