@@ -685,7 +685,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     f32x4{acc[mb][0][e], acc[mb][1][e], acc[mb][2][e], acc[mb][3][e]};
     }
 
-    constexpr int PU = MB == 1 ? 7 : 3;                   // split-K units (beside the block's own) the short way out adds
+    constexpr int PU = 7;                                  // split-K units (beside the block's own) the short way out adds
     // The common decode case gets a short, nearly branch-free way out (code that runs once per
     // launch is paid for by the instruction fetch, so its length is its cost): a finishing block
     // whose LoRA term, if any, was prefetched above and whose K has at most PU + 1 units.
