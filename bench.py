@@ -31,7 +31,7 @@ METRIC = "µs per multi-LoRA W4 linear + achieved HBM GB/s (% of 8 TB/s), 1 MI35
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by a copy kernel of known size; see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC = {"c2": 49004947}     # bytes per launch: profiles/layer_kernel_c2_hbm_traffic.txt
+MEASURED_TRAFFIC = {"c2": 49030614}     # bytes per launch: profiles/layer_kernel_c2_hbm_traffic.txt
 
 
 def parse_args():
