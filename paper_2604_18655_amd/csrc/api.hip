@@ -276,6 +276,11 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
             d.ctr_copies = 1;
             while (d.ctr_copies * 2 <= CTR_REPL && d.ctr_copies * 2 <= d.n_finish_blocks) d.ctr_copies *= 2;
             d.tiles_inv = (unsigned)((0x100000000ull + (unsigned)tiles_n(p.N) - 1) / (unsigned)tiles_n(p.N));
+            // (the division by multiplication is exact while index * tiles < 2^32: a projection
+            // with more than 2^15 column tiles and K units to match is refused rather than mis-indexed)
+            if ((unsigned long long)tiles_n(p.N) * (unsigned long long)tiles_n(p.N) * (unsigned long long)d.ksplit >=
+                0x100000000ull)
+                return MLORA_ESHAPE;
             // base blocks: one per column tile, or per four of them in the wide kernel
             const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
             a.main_begin[i] = main_blocks;
