@@ -165,8 +165,10 @@ __device__ __forceinline__ void round_issue_w(RoundW<R> &rw, const uint4 *codes_
     for (int i = 0; i < R; ++i) rw.w[i] = __builtin_nontemporal_load(wp + (in ? i * 64 : 0));   // (read once)
     // the round's groups are contiguous: 128 bytes each, lane l takes bytes 16*l.. (past the
     // round's last group the blob's slack keeps the read in bounds)
+    // (R / spg groups of 128 bytes: the lanes beyond them re-read the first 16 bytes)
+    const bool mine = lane < (R / spg) * 8;
     rw.sc = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(scales_tile) +
-                                       (in ? (size_t)(ks / spg) * 8 + lane : 0));
+                                       (in ? (size_t)(ks / spg) * 8 + (mine ? lane : 0) : 0));
 }
 
 // Request the rows of x (clamped to the chunk's rows and to K) of one round.
