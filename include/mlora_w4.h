@@ -58,7 +58,8 @@ enum {
 };
 
 /* One projection.  K = input features, N = output features.
- *   K % 128 == 0, group in {32, 64, 128}, N >= 1.
+ *   K % 128 == 0 (the kernels consume inputs four MFMA steps of 32 at a time), group in
+ *   {32, 64, 128}, N >= 1.
  *   w_blob   prepacked base weight made by mlora_w4_prepack (opaque, mlora_w4_blob_bytes bytes)
  *   lora_a   bf16 [n_adapters][rank][K]     (the paper's LoRA-A, transposed)
  *   lora_b   bf16 [n_adapters][N][rank]     (the paper's LoRA-B, transposed)
@@ -105,16 +106,36 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
 /* Device scratch a call over these projections and M rows needs (256-byte aligned pointer).
  * It holds what blocks of one launch hand to each other: the inner LoRA factor t[m] = A[a(m)].x[m]
  * of Eq. 1-4, partial base products of projections with more than 2048 inputs, and the
- * completion counters that order them.  The counters must be ZERO when a call starts and are
- * zero again when it ends: call mlora_w4_workspace_init once after allocating a workspace (or
- * hand in zero-filled memory); calls that overlap in time need a workspace each.  The first
- * uint32 of the workspace is a status word: it stays 0 unless a block gave up waiting for
- * another (which only a foreign write to the counters can cause); the results of that call are
- * then invalid and the workspace has to be initialised again. */
+ * completion counters that order them.
+ *  - Layout: a 256-byte header whose first uint32 is a status word, the counters growing from
+ *    the front, the data placed against the END of the workspace.  The size returned is
+ *    256 + 2 * max(counters, data), so that one workspace sized for the largest of several calls
+ *    (different projections, different M) serves all of them, one after another: no call's
+ *    counters can fall on another call's leftover data.  For that to hold, pass the SAME
+ *    workspace_bytes (the size of the allocation) on every call that uses a workspace.
+ *  - The counters must be ZERO when a call starts and are zero again when it ends: call
+ *    mlora_w4_workspace_init once after allocating a workspace (or hand in zero-filled memory).
+ *    Calls that overlap in time need a workspace each.
+ *  - Blocks of a launch are dispatched in index order and producers sit before their
+ *    consumers, so every wait ends; the waits are bounded all the same.  If one runs out
+ *    (only a foreign write to the counters, or a workspace that was not zero, can cause that), the
+ *    status word becomes non-zero, the outputs of the waiting block are stored as NaN, and the
+ *    workspace has to be initialised again.  mlora_w4_workspace_status reads the word. */
 size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M);
 
 /* Zero-fill a workspace (a small kernel on `stream`; no memset node, so it can be captured). */
 mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Copy the status word of a workspace to *status_word (HOST memory): 0 = every call since the
+ * last mlora_w4_workspace_init completed normally.  Unlike the other calls this one waits for
+ * `stream` (it has to, to hand a value back); do not call it under stream capture. */
+mlora_status mlora_w4_workspace_status(const void *workspace, int32_t *status_word, void *stream);
+
+/* Test hook: number of polls a waiting block makes before it gives up (default 200000;
+ * negative = back to the default; 0 = every wait gives up at once, which lets a test see the
+ * failure path -- status word, NaN outputs -- with every kernel still running to its end).
+ * Process-wide, read when a call is enqueued.  Returns the previous value. */
+int32_t mlora_w4_debug_spin_limit(int32_t limit);
 
 /* One projection.
  *   x            bf16 [M][K]
@@ -125,8 +146,9 @@ mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_
                              int32_t M, void *y, int32_t y_dtype, void *workspace,
                              size_t workspace_bytes, void *stream);
 
-/* Several independent projections over the same M rows and the same row->adapter index in as
- * one launch per 16 projections: the seven projections of a decoder block (Section 3.1), or more.
+/* Several independent projections over the same M rows and the same row->adapter index in
+ * one launch per 128 projections: the seven projections of a decoder block (Section 3.1), or
+ * those of many blocks at once.
  *   xs[i], ys[i]  device pointers of projection i (host arrays of n_proj pointers); inputs may
  *                 be shared (q, k, v read the same rows), outputs may not
  * Ordering against whatever produces the inputs is the caller's business. */

@@ -6,8 +6,9 @@ CPU fallback.  Loading fails loudly if the library has not been built
 """
 from .binding import (LayerPlan, MloraError, Proj, blob_bytes, group_rows, layer_step, lib_path, linear,
                       load_library, prepack, strerror, unpack, workspace_bytes,
-                      Y_BF16, Y_FP32, workspace_init, exported_symbols)
+                      Y_BF16, Y_FP32, workspace_init, workspace_status, debug_spin_limit,
+                      exported_symbols)
 
 __all__ = ["LayerPlan", "MloraError", "Proj", "blob_bytes", "group_rows", "layer_step", "lib_path", "linear",
            "load_library", "prepack", "strerror", "unpack", "workspace_bytes", "Y_BF16",
-           "Y_FP32", "workspace_init", "exported_symbols"]
+           "Y_FP32", "workspace_init", "workspace_status", "debug_spin_limit", "exported_symbols"]

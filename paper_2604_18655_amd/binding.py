@@ -15,7 +15,7 @@ Y_BF16, Y_FP32 = 0, 1
 exported_symbols = (
     "mlora_strerror", "mlora_w4_blob_bytes", "mlora_w4_prepack", "mlora_w4_unpack",
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
-    "mlora_w4_workspace_init",
+    "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
 )
 
 
@@ -64,6 +64,10 @@ def load_library():
                                             vp, sz, vp]
         lib.mlora_w4_workspace_init.restype = C.c_int
         lib.mlora_w4_workspace_init.argtypes = [vp, sz, vp]
+        lib.mlora_w4_workspace_status.restype = C.c_int
+        lib.mlora_w4_workspace_status.argtypes = [vp, C.POINTER(i32), vp]
+        lib.mlora_w4_debug_spin_limit.restype = i32
+        lib.mlora_w4_debug_spin_limit.argtypes = [i32]
         _lib = lib
     return _lib
 
@@ -138,6 +142,18 @@ def workspace_init(workspace) -> None:
     n = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().mlora_w4_workspace_init(_ptr(workspace), n, _stream()),
            "mlora_w4_workspace_init")
+
+
+def workspace_status(workspace) -> int:
+    """Status word of a workspace (0 = no block gave up waiting); waits for the current stream."""
+    word = C.c_int32(-1)
+    _check(load_library().mlora_w4_workspace_status(_ptr(workspace), C.byref(word), _stream()),
+           "mlora_w4_workspace_status")
+    return int(word.value)
+
+
+def debug_spin_limit(limit: int) -> int:
+    return int(load_library().mlora_w4_debug_spin_limit(int(limit)))
 
 
 def workspace_bytes(projs: Sequence[Proj], M: int) -> int:

@@ -1,6 +1,10 @@
 // C ABI of the mlora_w4 library: host-side validation, launch planning, no device allocation.
 #include <string.h>
 
+#include <algorithm>
+#include <memory>
+#include <vector>
+
 #include "common.hpp"
 
 using namespace mlora;
@@ -146,8 +150,8 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                              (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }
 
-// Projections of one launch: up to 16, and for the wide kernel (33 rows and more, compiled per
-// group size) only as long as the group size stays the same.
+// Projections of one launch: up to MAX_PROJ_PER_LAUNCH, and for the wide kernel (33 rows and
+// more, compiled per group size) only as long as the group size stays the same.
 static int launch_run(const mlora_w4_proj *projs, int n_left, int M)
 {
     int count = 1;
@@ -157,42 +161,158 @@ static int launch_run(const mlora_w4_proj *projs, int n_left, int M)
     return count;
 }
 
-// Workspace layout: [status word, 256 B][counters of launch 0][counters of launch 1]...[data].
-// Counters exist only if something is shared between blocks (LoRA or split-K).
-static size_t ctrl_bytes_of_launch(const mlora_w4_proj *projs, int count, int M, bool lora)
+// What one launch over projs[0 .. count) needs of the workspace, and (with `a`) its argument
+// block.  Counters: 16 lines per projection (copies of its shrink counter), then one line per
+// (column tile, row chunk) of every projection whose K is cut into several units.  Data: per
+// projection the split-K partial tiles, then the shrink step's partial sums.  Both passes of a
+// call (sizes first, arguments second) go through this one function.
+struct LaunchNeed {
+    size_t ctrl_bytes, data_bytes;
+    int grid_x, groups;
+};
+
+static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *xs, void *const *ys,
+                                int count, int M, bool lora_on, LaunchNeed &need, LayerArgs *a,
+                                char *ctrl, char *data)
 {
-    size_t n = 0;                              // counter lines of the split-K tiles
-    bool any = false;
-    for (int i = 0; i < count; ++i) {
-        if (ksplit_of(projs[i], M, launch_blocks_of(projs, count, M)) > 1) {
-            n += (size_t)tiles_n(projs[i].N) * (size_t)(m_pad_of(M) / rows_per_chunk(M));
-            any = true;
-        }
-        any = any || (lora && projs[i].n_adapters > 0);
+    const int chunks = m_pad_of(M) / rows_per_chunk(M);
+    const int lb = launch_blocks_of(projs, count, M);
+    const int groups = (count + GROUP_PROJ - 1) / GROUP_PROJ;
+    bool shared = false;                       // anything handed from block to block?
+    size_t part_lines = 0, data_bytes = 0;
+    int part_ctr = count * CTR_REPL * CTR_STRIDE;
+    int grid_x = 0;
+    if (a) {
+        for (int z = 0; z < MAX_GROUPS; ++z)
+            for (int i = 0; i < GROUP_PROJ; ++i)
+                a->main_begin[z][i] = a->pre_begin[z][i] = a->shrink_begin[z][i] = 0x7FFFFFFF;
     }
-    return any ? (CTRL_PART + n * CTR_STRIDE) * sizeof(unsigned) : 0;
+    for (int z = 0; z < groups; ++z) {
+        int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0;
+        for (int i = z * GROUP_PROJ; i < count && i < (z + 1) * GROUP_PROJ; ++i) {
+            const mlora_w4_proj &p = projs[i];
+            const int tiles = tiles_n(p.N);
+            const int ksplit = ksplit_of(p, M, lb);
+            // The kernels divide a block index by the tile count with a multiplication that is
+            // exact while index * tiles < 2^32: a projection with more than 2^15 column tiles and
+            // K units to match is refused rather than mis-indexed.
+            if ((unsigned long long)tiles * (unsigned long long)tiles * (unsigned long long)ksplit >= 0x100000000ull)
+                return MLORA_ESHAPE;
+            const bool lora = lora_on && p.n_adapters > 0;
+            // base blocks: one per column tile, or per four of them in the wide kernel
+            const int col_blocks = (tiles + tiles_per_block(M) - 1) / tiles_per_block(M);
+            const size_t part_bytes = partial_bytes(p, M, lb);
+            const size_t t_bytes = lora ? t_part_bytes(p, M) : 0;
+            const int n_shrink = !lora ? 0
+                : (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *
+                      (r16_of(p) / 16) * kch_of(p, M);
+            if (a) {
+                ProjArgs &d = a->p[i];
+                const int j = i - z * GROUP_PROJ;
+                d.codes = reinterpret_cast<const uint4 *>(p.w_blob);
+                d.scales = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(p.w_blob) +
+                                                           blob_code_bytes(p.K, p.N));
+                d.x = reinterpret_cast<const uint16_t *>(xs[i]);
+                d.y = ys[i];
+                d.K = p.K;
+                d.N = p.N;
+                d.spg = p.group / KSTEP;
+                d.alpha = p.alpha;
+                d.ksplit = ksplit;
+                // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
+                // finishing ones, or every K unit where the LoRA term is spread over them
+                d.n_finish_blocks = tiles * chunks * (M >= WIDE_MIN_ROWS ? ksplit : 1);
+                d.unit_q = (p.K / SUPER_K) / ksplit;
+                d.unit_r = (p.K / SUPER_K) % ksplit;
+                d.spg_shift = d.spg == 4 ? 2 : d.spg == 2 ? 1 : 0;
+                d.ctr_copies = 1;
+                while (d.ctr_copies * 2 <= CTR_REPL && d.ctr_copies * 2 <= d.n_finish_blocks) d.ctr_copies *= 2;
+                d.tiles_inv = (unsigned)((0x100000000ull + (unsigned)tiles - 1) / (unsigned)tiles);
+                a->main_begin[z][j] = main_blocks;
+                a->pre_begin[z][j] = pre_blocks;
+                a->shrink_begin[z][j] = shrink_blocks;
+                d.partial = reinterpret_cast<float *>(data + data_bytes);
+                d.part_ctr = part_ctr;
+                if (lora) {
+                    d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);
+                    d.lora_b = reinterpret_cast<const uint16_t *>(p.lora_b);
+                    d.n_adapters = p.n_adapters;
+                    d.rank = p.rank;
+                    d.r16 = r16_of(p);
+                    d.kch = kch_of(p, M);
+                    d.t_part = reinterpret_cast<float *>(data + data_bytes + part_bytes);
+                    d.n_shrink_blocks = n_shrink;
+                } else {
+                    d.n_adapters = 0;
+                    d.rank = 0;
+                    d.r16 = 16;
+                    d.kch = 1;
+                }
+            }
+            main_blocks += col_blocks;
+            pre_blocks += col_blocks * (ksplit - 1);
+            shrink_blocks += n_shrink;
+            data_bytes += part_bytes + t_bytes;
+            if (ksplit > 1) {
+                part_ctr += tiles * chunks * CTR_STRIDE;
+                part_lines += (size_t)tiles * (size_t)chunks;
+            }
+            shared = shared || ksplit > 1 || lora;
+        }
+        const int total = shrink_blocks + pre_blocks + main_blocks;
+        if (a) {
+            a->shrink_blocks[z] = shrink_blocks;
+            a->pre_base_blocks[z] = pre_blocks;
+            a->group_blocks[z] = total;
+        }
+        if (total > grid_x) grid_x = total;
+    }
+    need.ctrl_bytes = shared ? ((size_t)count * CTR_REPL + part_lines) * CTR_STRIDE * sizeof(unsigned) : 0;
+    need.data_bytes = data_bytes;
+    need.grid_x = grid_x;
+    need.groups = groups;
+    if (a) a->ctrl = reinterpret_cast<unsigned *>(ctrl);
+    return MLORA_OK;
 }
 
-static size_t ctrl_bytes_total(const mlora_w4_proj *projs, int n_proj, int M, bool lora)
+// Sizes of a whole call (all its launches).
+static mlora_status plan_call(const mlora_w4_proj *projs, int n_proj, int M, bool lora_on,
+                              size_t &ctrl_total, size_t &data_total)
 {
-    size_t total = 0;
+    ctrl_total = data_total = 0;
     for (int first = 0, count = 0; first < n_proj; first += count) {
         count = launch_run(projs + first, n_proj - first, M);
-        total += ctrl_bytes_of_launch(projs + first, count, M, lora);
+        LaunchNeed need;
+        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, lora_on, need, nullptr, nullptr, nullptr);
+        if (st != MLORA_OK) return st;
+        ctrl_total += need.ctrl_bytes;
+        data_total += need.data_bytes;
     }
-    return total ? total + WS_HEADER_BYTES : 0;
+    return MLORA_OK;
+}
+
+// Workspace layout: [status word, 256 B][counters of launch 0, 1, ...] ... [data of launch 0, 1, ...]
+// with the data at the END of the workspace as handed in.  Counters must read zero when a call
+// starts and return to zero by themselves; data is never cleared.  Were the data to follow the
+// counters directly, a later call with more counter lines (another shape, more rows) would find
+// its extra lines inside the earlier call's data.  With the counters growing from the front, the
+// data placed against the end, and a size of 256 + 2 * max(counters, data), the counters of any
+// call and the data of any other call that fits the same workspace cannot overlap.
+static size_t workspace_need(size_t ctrl_total, size_t data_total)
+{
+    if (ctrl_total == 0) return 0;
+    const size_t c = round_up(ctrl_total, 256), d = round_up(data_total, 256);
+    return WS_HEADER_BYTES + 2 * (c > d ? c : d);
 }
 
 size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M)
 {
-    if (!projs || n_proj <= 0 || M <= 0) return 0;
-    size_t total = ctrl_bytes_total(projs, n_proj, M, true);
-    for (int first = 0, count = 0; first < n_proj; first += count) {
-        count = launch_run(projs + first, n_proj - first, M);
-        const int lb = launch_blocks_of(projs + first, count, M);
-        for (int i = first; i < first + count; ++i) total += t_part_bytes(projs[i], M) + partial_bytes(projs[i], M, lb);
-    }
-    return total;
+    if (!projs || n_proj <= 0 || M <= 0 || M > MLORA_MAX_ROWS) return 0;
+    for (int i = 0; i < n_proj; ++i)
+        if (check_weight_shape(projs[i].K, projs[i].N, projs[i].group) != MLORA_OK) return 0;
+    size_t ctrl_total, data_total;
+    if (plan_call(projs, n_proj, M, true, ctrl_total, data_total) != MLORA_OK) return 0;
+    return workspace_need(ctrl_total, data_total);
 }
 
 mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
@@ -203,121 +323,101 @@ mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, vo
                ? MLORA_OK : MLORA_EHIP;
 }
 
-mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
-                                 const void *const *xs, void *const *ys,
-                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
-                                 void *workspace, size_t workspace_bytes, void *stream)
+mlora_status mlora_w4_workspace_status(const void *workspace, int32_t *status_word, void *stream)
+{
+    if (!workspace || !status_word) return MLORA_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned word = 0;
+    if (hipMemcpyAsync(&word, workspace, sizeof word, hipMemcpyDeviceToHost, s) != hipSuccess) return MLORA_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return MLORA_EHIP;
+    *status_word = (int32_t)word;
+    return MLORA_OK;
+}
+
+static int g_spin_limit = SPIN_LIMIT_DEFAULT;
+
+int32_t mlora_w4_debug_spin_limit(int32_t limit)
+{
+    const int old = g_spin_limit;
+    g_spin_limit = limit < 0 ? SPIN_LIMIT_DEFAULT : limit;
+    return old;
+}
+
+// Host-side checks of a call: everything that can be refused is refused here, before the first launch.
+static mlora_status check_call(const mlora_w4_proj *projs, int32_t n_proj, const void *const *xs,
+                               void *const *ys, const int32_t *row_adapter, int32_t M, int32_t y_dtype)
 {
     if (!projs || !xs || !ys || n_proj <= 0) return MLORA_EINVAL;
     if (y_dtype != MLORA_Y_BF16 && y_dtype != MLORA_Y_FP32) return MLORA_EINVAL;
     if (M < 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
-    bool any_lora = false;
     for (int i = 0; i < n_proj; ++i) {
         mlora_status st = check_proj(projs[i]);
         if (st != MLORA_OK) return st;
         if (!xs[i] || !ys[i]) return MLORA_EINVAL;
         if (!aligned16(xs[i]) || !aligned16(ys[i])) return MLORA_EALIGN;
-        for (int j = 0; j < i; ++j)
-            if (ys[j] == ys[i]) return MLORA_EINVAL;
-        any_lora = any_lora || projs[i].n_adapters > 0;
     }
-    if (M == 0) return MLORA_OK;
-    any_lora = any_lora && row_adapter != nullptr;
+    // outputs may not be shared (sorted copy: a call may bring thousands of projections)
+    std::vector<const void *> outs(ys, ys + n_proj);
+    std::sort(outs.begin(), outs.end());
+    if (std::adjacent_find(outs.begin(), outs.end()) != outs.end()) return MLORA_EINVAL;
     if (row_adapter && (reinterpret_cast<uintptr_t>(row_adapter) & 3u)) return MLORA_EALIGN;
-    const size_t need = mlora_w4_workspace_bytes(projs, n_proj, M);
+    return MLORA_OK;
+}
+
+// Enqueue the launches of a checked call on a workspace whose counters read zero.
+static mlora_status enqueue_call(const mlora_w4_proj *projs, int32_t n_proj, const void *const *xs,
+                                 void *const *ys, const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 bool lora_on, char *workspace, size_t workspace_bytes, size_t data_total,
+                                 hipStream_t s)
+{
+    char *ctrl = workspace ? workspace + WS_HEADER_BYTES : nullptr;
+    char *data = workspace ? workspace + workspace_bytes / 256 * 256 - round_up(data_total, 256) : nullptr;
+    // (one argument block on the heap: it is about 19 KiB and is copied by the launch)
+    std::unique_ptr<LayerArgs> a(new LayerArgs);
+    for (int first = 0, count = 0; first < n_proj; first += count) {
+        count = launch_run(projs + first, n_proj - first, M);
+        memset(a.get(), 0, sizeof(LayerArgs));
+        a->row_adapter = lora_on ? row_adapter : nullptr;
+        a->n_proj = count;
+        a->M = M;
+        a->y_fp32 = (y_dtype == MLORA_Y_FP32);
+        a->m_pad = m_pad_of(M);
+        a->spin_limit = g_spin_limit;
+        a->code_mask = 0x00780078u;
+        a->code_bias = 0x41804180u;
+        a->status = reinterpret_cast<unsigned *>(workspace);
+        LaunchNeed need;
+        const mlora_status st = plan_launch(projs + first, xs + first, ys + first, count, M, lora_on, need,
+                                            a.get(), ctrl, data);
+        if (st != MLORA_OK) return st;         // (cannot happen: the sizing pass has seen the same shapes)
+        if (launch_layer(*a, need.grid_x, need.groups, s) != hipSuccess) return MLORA_EHIP;
+        ctrl += need.ctrl_bytes;
+        data += need.data_bytes;
+    }
+    return MLORA_OK;
+}
+
+mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                 const void *const *xs, void *const *ys,
+                                 const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    mlora_status st = check_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype);
+    if (st != MLORA_OK) return st;
+    if (M == 0) return MLORA_OK;
+    size_t ctrl_total, data_total;
+    st = plan_call(projs, n_proj, M, true, ctrl_total, data_total);
+    if (st != MLORA_OK) return st;
+    const size_t need = workspace_need(ctrl_total, data_total);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return MLORA_EWORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
     }
-
-    hipStream_t s = (hipStream_t)stream;
-    char *ctrl = reinterpret_cast<char *>(workspace) + WS_HEADER_BYTES;
-    char *ws = reinterpret_cast<char *>(workspace) + ctrl_bytes_total(projs, n_proj, M, true);
-    const int chunks = m_pad_of(M) / rows_per_chunk(M);
-    for (int first = 0, count = 0; first < n_proj; first += count) {
-        count = launch_run(projs + first, n_proj - first, M);
-        LayerArgs a;
-        memset(&a, 0, sizeof a);
-        a.row_adapter = any_lora ? row_adapter : nullptr;
-        a.n_proj = count;
-        a.M = M;
-        a.y_fp32 = (y_dtype == MLORA_Y_FP32);
-        for (int i = 0; i < MAX_PROJ_PER_LAUNCH; ++i)
-            a.main_begin[i] = a.pre_begin[i] = a.shrink_begin[i] = 0x7FFFFFFF;
-        a.m_pad = m_pad_of(M);
-        a.code_mask = 0x00780078u;
-        a.code_bias = 0x41804180u;
-        if (need > 0) {
-            a.status = reinterpret_cast<unsigned *>(workspace);
-            a.ctrl = reinterpret_cast<unsigned *>(ctrl);
-            ctrl += ctrl_bytes_of_launch(projs + first, count, M, true);
-        }
-        const int lb = launch_blocks_of(projs + first, count, M);
-        int main_blocks = 0, pre_blocks = 0, shrink_blocks = 0, part_ctr = CTRL_PART;
-        for (int i = 0; i < count; ++i) {
-            const mlora_w4_proj &p = projs[first + i];
-            ProjArgs &d = a.p[i];
-            d.codes = reinterpret_cast<const uint4 *>(p.w_blob);
-            d.scales = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(p.w_blob) +
-                                                       blob_code_bytes(p.K, p.N));
-            d.x = reinterpret_cast<const uint16_t *>(xs[first + i]);
-            d.y = ys[first + i];
-            d.K = p.K;
-            d.N = p.N;
-            d.spg = p.group / KSTEP;
-            d.alpha = p.alpha;
-            d.ksplit = ksplit_of(p, M, lb);
-            // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
-            // finishing ones, or every K unit where the LoRA term is spread over them
-            d.n_finish_blocks = tiles_n(p.N) * chunks * (M >= WIDE_MIN_ROWS ? d.ksplit : 1);
-            d.unit_q = (p.K / SUPER_K) / d.ksplit;
-            d.unit_r = (p.K / SUPER_K) % d.ksplit;
-            d.spg_shift = d.spg == 4 ? 2 : d.spg == 2 ? 1 : 0;
-            d.ctr_copies = 1;
-            while (d.ctr_copies * 2 <= CTR_REPL && d.ctr_copies * 2 <= d.n_finish_blocks) d.ctr_copies *= 2;
-            d.tiles_inv = (unsigned)((0x100000000ull + (unsigned)tiles_n(p.N) - 1) / (unsigned)tiles_n(p.N));
-            // (the division by multiplication is exact while index * tiles < 2^32: a projection
-            // with more than 2^15 column tiles and K units to match is refused rather than mis-indexed)
-            if ((unsigned long long)tiles_n(p.N) * (unsigned long long)tiles_n(p.N) * (unsigned long long)d.ksplit >=
-                0x100000000ull)
-                return MLORA_ESHAPE;
-            // base blocks: one per column tile, or per four of them in the wide kernel
-            const int col_blocks = (tiles_n(p.N) + tiles_per_block(M) - 1) / tiles_per_block(M);
-            a.main_begin[i] = main_blocks;
-            main_blocks += col_blocks;
-            a.pre_begin[i] = pre_blocks;
-            pre_blocks += col_blocks * (d.ksplit - 1);
-            d.partial = reinterpret_cast<float *>(ws);
-            ws += partial_bytes(p, M, lb);
-            d.part_ctr = part_ctr;
-            if (d.ksplit > 1) part_ctr += tiles_n(p.N) * chunks * CTR_STRIDE;
-            a.shrink_begin[i] = shrink_blocks;
-            if (any_lora && p.n_adapters > 0) {
-                d.lora_a = reinterpret_cast<const uint16_t *>(p.lora_a);
-                d.lora_b = reinterpret_cast<const uint16_t *>(p.lora_b);
-                d.n_adapters = p.n_adapters;
-                d.rank = p.rank;
-                d.r16 = r16_of(p);
-                d.kch = kch_of(p, M);
-                d.t_part = reinterpret_cast<float *>(ws);
-                ws += t_part_bytes(p, M);
-                // at most 16 rows: a shrink block per row; above: per 16-row tile of an adapter segment
-                d.n_shrink_blocks = (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS *
-                                                          shrink_tile_shares(M, p.n_adapters)) *
-                                    (d.r16 / 16) * d.kch;
-                shrink_blocks += d.n_shrink_blocks;
-            } else {
-                d.n_adapters = 0;
-                d.rank = 0;
-                d.r16 = 16;
-                d.kch = 1;
-            }
-        }
-        a.shrink_blocks = shrink_blocks;
-        a.pre_base_blocks = pre_blocks;
-        if (launch_layer(a, shrink_blocks + pre_blocks + main_blocks, s) != hipSuccess) return MLORA_EHIP;
-    }
-    return MLORA_OK;
+    bool any_lora = false;
+    for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
+    return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
+                        need > 0 ? reinterpret_cast<char *>(workspace) : nullptr, workspace_bytes, data_total,
+                        (hipStream_t)stream);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,

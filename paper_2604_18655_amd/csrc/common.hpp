@@ -51,9 +51,14 @@ __host__ __device__ inline uint32_t rotl32(uint32_t v, int s) {
 __host__ __device__ inline uint32_t rotr32(uint32_t v, int s) { return rotl32(v, 32 - (s & 31)); }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel argument block of one grouped call (passed by value, < 4 KiB).
+// Kernel argument block of one grouped call (passed by value: about 19 KiB; a block reads only
+// the launch scalars, the three table rows of its group and the record of its projection).
+// The projections of a launch are cut into groups of up to 16; group z owns slice z of the grid
+// (blockIdx.z) and the block tables of a group are one vector of 16 each.
 // ---------------------------------------------------------------------------------------------
-constexpr int MAX_PROJ_PER_LAUNCH = 16;
+constexpr int GROUP_PROJ = 16;
+constexpr int MAX_GROUPS = 8;
+constexpr int MAX_PROJ_PER_LAUNCH = GROUP_PROJ * MAX_GROUPS;
 constexpr int ROWS_PER_BLOCK16 = 16;
 constexpr int MAX_KCHUNKS = 16;    // partial sums of the shrink step the epilogue adds up
 
@@ -97,23 +102,26 @@ struct ProjArgs {
 constexpr int CTR_REPL = 16;
 constexpr int CTR_STRIDE = 32;                 // uint32 per counter line
 __host__ __device__ inline int shrink_ctr(int p, int r) { return (p * CTR_REPL + r) * CTR_STRIDE; }
-constexpr int CTRL_PART = MAX_PROJ_PER_LAUNCH * CTR_REPL * CTR_STRIDE;
 constexpr size_t WS_HEADER_BYTES = 256;        // status word at the front of every workspace
+constexpr int SPIN_LIMIT_DEFAULT = 200000;     // x ~0.5 us: far beyond any launch, still finite
 
 struct LayerArgs {
-    // One launch holds, in this order, the shrink blocks, the split-K blocks (units 1..) and the
-    // finishing blocks (unit 0) of all projections; first block of each projection in each group:
-    int shrink_begin[MAX_PROJ_PER_LAUNCH];
-    int pre_begin[MAX_PROJ_PER_LAUNCH];
-    int main_begin[MAX_PROJ_PER_LAUNCH];
+    // Slice z of the grid holds, in this order, the shrink blocks, the split-K blocks (units 1..)
+    // and the finishing blocks (unit 0) of the projections of group z; first block of each
+    // projection within its kind (entries past the group's last projection: INT_MAX):
+    int shrink_begin[MAX_GROUPS][GROUP_PROJ];
+    int pre_begin[MAX_GROUPS][GROUP_PROJ];
+    int main_begin[MAX_GROUPS][GROUP_PROJ];
     ProjArgs p[MAX_PROJ_PER_LAUNCH];
+    int shrink_blocks[MAX_GROUPS];     // shrink blocks of the group (first in its slice)
+    int pre_base_blocks[MAX_GROUPS];   // split-K blocks of the group (after its shrink blocks)
+    int group_blocks[MAX_GROUPS];      // all blocks of the group; the slice's other blocks exit at once
     const int *row_adapter;    // may be null
     int n_proj;
     int M;
     int y_fp32;
     int m_pad;                 // M rounded up to whole row chunks of the base kernel
-    int shrink_blocks;         // number of shrink blocks (first in the grid)
-    int pre_base_blocks;       // number of split-K blocks (after the shrink blocks)
+    int spin_limit;            // polls a block makes before it gives up waiting (0: gives up at once)
     unsigned *ctrl;            // completion counters of this launch
     unsigned *status;          // workspace status word: set non-zero if a wait ran out
     uint32_t code_mask;        // 0x00780078: the two code fields of a bf16 pair
@@ -166,22 +174,6 @@ __host__ __device__ inline int shrink_tile_shares(int M, int n_adapters)
     return (M > 32 && M < 2 * SHRINK_CHUNK_ROWS) ? (tiles + 3) / 4 : (tiles + 15) / 16;
 }
 
-// Timeline probes for kernel tuning: compiled in only with -DMLORA_TRACE (never in the
-// library build); each wave appends (constant-rate clock, shader clock) pairs to a buffer.
-#ifdef MLORA_TRACE
-extern __device__ unsigned long long *g_trace;           // [g_trace_slots][32]
-extern __device__ unsigned long long g_trace_slots;      // a wave beyond the buffer records nothing
-#define MLORA_TRACE_POINT(slot, id)                                                        \
-    do {                                                                                   \
-        if (g_trace && (threadIdx.x & 63) == 0 && (unsigned long long)(slot) < g_trace_slots) { \
-            g_trace[(size_t)(slot) * 32 + 2 * (id)] = wall_clock64();                      \
-            g_trace[(size_t)(slot) * 32 + 2 * (id) + 1] = clock64();                       \
-        }                                                                                  \
-    } while (0)
-#else
-#define MLORA_TRACE_POINT(slot, id) do { } while (0)
-#endif
-
 // host launchers (each file defines its own)
 hipError_t launch_prepack(int K, int N, int group, const uint8_t *wq, const uint16_t *scales,
                           void *blob, hipStream_t s);
@@ -189,7 +181,7 @@ hipError_t launch_unpack(int K, int N, int group, const void *blob, int8_t *code
                          hipStream_t s);
 hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int *perm,
                              int *seg_adapter, int *seg_start, int *n_seg, hipStream_t s);
-hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s);
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)

@@ -26,22 +26,9 @@
 
 namespace mlora {
 
-#ifdef MLORA_TRACE
-__device__ unsigned long long *g_trace = nullptr;
-__device__ unsigned long long g_trace_slots = 0;          // waves the buffer has room for
-extern "C" hipError_t mlora_trace_set(unsigned long long *p, unsigned long long n_slots)
-{
-    const unsigned long long n = p ? n_slots : 0;
-    const hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(g_trace_slots), &n, sizeof n);
-    return e != hipSuccess ? e : hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof p);
-}
-#endif
-
 // ------------------------------------------------------------------------------------------
 // completion counters
 // ------------------------------------------------------------------------------------------
-constexpr int SPIN_LIMIT = 200000;            // x ~0.5 us: far beyond any launch, still finite
-
 // Data one block hands to another inside a launch (split-K partial tiles, the shrink step's t)
 // is written and read with agent-scope accesses: they go through to memory and are re-fetched
 // from it, so no cache of a compute unit or of a die ever holds a stale copy of it, and no
@@ -79,23 +66,35 @@ __device__ __forceinline__ void shared16_wait(f32x4_t (&v)[16])
                  : "memory");
 }
 
+// The hardware keeps the order "data, then counter" on the producer's side (the wait for the
+// stores' acknowledgements below) and "counter, then data" on the consumer's (a wave's loads are
+// issued in program order, and these go through to memory).  The compiler must keep it too:
+// relaxed accesses to different addresses may be reordered, so a compiler-only fence (no
+// instruction, no cache action) stands between the data accesses and the counter access.
+__device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
+
 // all threads of the block, after their store_shared calls: wait until the own stores have been
 // acknowledged, meet, then count the block as done in `copies` counter lines
 __device__ __forceinline__ void signal_done(unsigned *counter, int copies)
 {
+    compiler_fence();
     __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): every store of this wave has completed
     __syncthreads();
     if ((int)threadIdx.x < copies) atomicAdd(counter + threadIdx.x * CTR_STRIDE, 1u);
 }
 
-// one thread: wait until *counter has reached expected; false if the wait ran out
-__device__ __forceinline__ bool wait_count(unsigned *counter, unsigned expected)
+// Wait until *counter has reached expected, polling at most `limit` times; false if the wait ran
+// out (limit 0: at once).  Reads of what the counter guards must come after this call: the
+// fence keeps the compiler from moving them up.
+__device__ __forceinline__ bool wait_count(unsigned *counter, unsigned expected, int limit)
 {
-    for (int i = 0; i < SPIN_LIMIT; ++i) {
-        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) return true;
+    bool ok = false;
+    for (int i = 0; i < limit; ++i) {
+        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) { ok = true; break; }
         __builtin_amdgcn_s_sleep(1);
     }
-    return false;
+    compiler_fence();
+    return ok;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -458,8 +457,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const int K = P.K, N = P.N, M = a.M;
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int l16 = lane & 15, lq = lane >> 4;
-    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * WAVES + wave;
-    MLORA_TRACE_POINT(trace_slot, 0);
     // the units of a split projection form the longest chain of the launch: they go first
     // wherever they share a SIMD with other waves
     if (P.ksplit > 1) __builtin_amdgcn_s_setprio(2);
@@ -501,7 +498,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    MLORA_TRACE_POINT(trace_slot, 1);
 
     // epilogue operands fetched while the last round is being computed: the rows of B of this
     // thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
@@ -602,11 +598,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         for (int i = 0; i < XR; ++i) *reinterpret_cast<u32x4 *>(buf + lane * 16 + i * L::XROW) = xr[i];
         const unsigned *dummy = reinterpret_cast<const unsigned *>(wp);
         const unsigned *poll_s = need_s ? sctr : dummy, *poll_p = need_p ? pctr : dummy;
-        MLORA_TRACE_POINT(trace_slot, 7);
         if (P.spg == 1)      stream_loop<1>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
         else if (P.spg == 2) stream_loop<2>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
         else                 stream_loop<4>(acc[0], sa, sb, wp, sp, my_cnt, xl, mask, bias, lane, poll_s, poll_p, seen_s, seen_p);
-        MLORA_TRACE_POINT(trace_slot, 6);
         // Everything below derives its indices afresh from the thread id: values shared with the
         // code above the loop would have to live across it, in registers the loop needs.
         asm volatile("" : "+v"(tid));
@@ -628,7 +622,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         round_issue_x<XR, R>(xr, P.x, K, m0, rows_x, ks_first, true, lane);
         // (keeps all of these requests ahead of the first wait)
         __builtin_amdgcn_sched_barrier(0);
-        MLORA_TRACE_POINT(trace_slot, 7);
         auto compute = [&](int n) {
             if (P.spg == 1)      round_compute<MB, XR, R, 1>(acc, buf, n, rows_x, mask, bias, lane);
             else if (P.spg == 2) round_compute<MB, XR, R, 2>(acc, buf, n, rows_x, mask, bias, lane);
@@ -642,7 +635,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             // (the scheduler would otherwise sink the requests below the math to save registers)
             __builtin_amdgcn_sched_barrier(0);
             compute(r0 < nr ? R : 0);
-            MLORA_TRACE_POINT(trace_slot, 6);
             round_to_lds<XR, R>(wb, xr, buf, lane);
             round_issue_w<R>(wb, codes_tile, scales_tile, P.spg, ks_first + (r0 + 3) * R, r0 + 3 < nr, lane);
             round_issue_x<XR, R>(xr, P.x, K, m0, rows_x, ks_first + (r0 + 2) * R, r0 + 2 < nr, lane);
@@ -661,18 +653,23 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         pf.issue();
     }
 
-    MLORA_TRACE_POINT(trace_slot, 2);
     // Above 16 rows the partial tiles and t lie over the staging buffers of all waves: meet first.
     if constexpr (!BaseLds<MB, XR, WAVES, R>::PRIVATE) __syncthreads();
     // What the epilogue reads from other blocks.  Every wave makes sure of it for itself (all
     // lanes poll the same word), unless the look during its last super-step already showed it.
+    // A wave whose wait runs out sets the workspace's status word and stores NaN in place of its
+    // outputs: a call that went wrong must not look like one that went right.
+    bool poisoned = false;
     {
+        const int limit = a.spin_limit;
         bool ok = true;
-        if (need_s && seen_s < (unsigned)P.n_shrink_blocks) ok = wait_count(sctr, (unsigned)P.n_shrink_blocks);
-        if (need_p && seen_p < (unsigned)(P.ksplit - 1)) ok = wait_count(pctr, (unsigned)(P.ksplit - 1)) && ok;
+        if (need_s && (limit == 0 || seen_s < (unsigned)P.n_shrink_blocks)) ok = wait_count(sctr, (unsigned)P.n_shrink_blocks, limit);
+        if (need_p && (limit == 0 || seen_p < (unsigned)(P.ksplit - 1))) ok = wait_count(pctr, (unsigned)(P.ksplit - 1), limit) && ok;
+        compiler_fence();
         if (!ok && lane == 0) atomicOr(a.status, 1u);
+        poisoned = !ok;
     }
-    MLORA_TRACE_POINT(trace_slot, 8);
+    const float nan_f = __uint_as_float(0x7FC00000u);
 
     // partial tiles -> LDS: element (mb, j, e) of lane l at red_at(mb, e, l) + j, so that the thread
     // that finishes e of every j reads four of them at once
@@ -721,9 +718,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                         for (int u = 3; u < PU; ++u) pv[qq][u] = 0.f;
                 }
             }
-            MLORA_TRACE_POINT(trace_slot, 3);
             __syncthreads();
-            MLORA_TRACE_POINT(trace_slot, 4);
             const int n0 = tile * TILE_N + l16;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
@@ -755,6 +750,8 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     }
                 }
                 const int m = m0 + elem_ml(4 * mb);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = poisoned ? nan_f : v[j];
                 if (m < M) {
                     if (a.y_fp32) {
                         float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;
@@ -799,9 +796,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                 lds.t_row(ml)[jj] = v * P.alpha;
             }
         }
-        MLORA_TRACE_POINT(trace_slot, 3);
         __syncthreads();
-        MLORA_TRACE_POINT(trace_slot, 4);
 
 #pragma unroll
         for (int qq = 0; qq < EPT; ++qq) {
@@ -837,6 +832,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     }
                     v += l;
                 }
+                v = poisoned ? nan_f : v;
                 if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
                 else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
             }
@@ -853,7 +849,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             __hip_atomic_store(sctr + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    MLORA_TRACE_POINT(trace_slot, 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -885,8 +880,6 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     using L = ShrinkLds;
     constexpr int SB = L::SB;
     GroupLds64 &g = lds.g;
-    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
-    MLORA_TRACE_POINT(trace_slot, 0);
     const int jblocks = P.r16 / 16;
     const int shares = shrink_tile_shares(a.M, P.n_adapters);
     const int kc = local % P.kch;
@@ -896,7 +889,6 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
     const int m_base = chunk * SHRINK_CHUNK_ROWS;
 
     group_rows_lds64(a.row_adapter + m_base, min(SHRINK_CHUNK_ROWS, a.M - m_base), P.n_adapters, g);
-    MLORA_TRACE_POINT(trace_slot, 1);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
@@ -981,7 +973,6 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
         }
     }
     signal_done(a.ctrl + shrink_ctr(pi, 0), P.ctr_copies);
-    MLORA_TRACE_POINT(trace_slot, 5);
 }
 
 
@@ -1008,8 +999,6 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
 {
     using L = ShrinkRowLds;
     constexpr int SB = L::SB;
-    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
-    MLORA_TRACE_POINT(trace_slot, 0);
     const int jblocks = P.r16 / 16;
     const int kc = local % P.kch;
     const int jb = (local / P.kch) % jblocks;
@@ -1032,7 +1021,6 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
     const uint16_t *xrow = P.x + (size_t)m * P.K + (size_t)my_beg * KSTEP + l32 * 8;
     const uint16_t *arow = P.lora_a + (size_t)(valid ? adapter : 0) * P.rank * P.K + (size_t)my_beg * KSTEP + l32 * 8;
     unsigned char *la = lds.a[wave], *lx = lds.x[wave];
-    MLORA_TRACE_POINT(trace_slot, 1);
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < my_cnt && valid; s0 += SB) {
@@ -1069,7 +1057,6 @@ __device__ __forceinline__ void shrink_row_block(const LayerArgs &a, const ProjA
     }
     // (a base-only row has nothing to write, but the finishing blocks count its blocks all the same)
     signal_done(a.ctrl + shrink_ctr(pi, 0), P.ctr_copies);
-    MLORA_TRACE_POINT(trace_slot, 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1106,26 +1093,30 @@ __device__ __forceinline__ ProjArgs fetch_proj(const LayerArgs &a, int pi)
     return P;
 }
 
-// The three block tables and the scalar fields at the end of the launch arguments, all requested
-// together at the kernel's start: one scalar round trip (the cache behind the kernel arguments
-// is cold at every launch) instead of one for the scalars, a dependent one for the table of the
-// block's kind and then the projection's record.  Left alone, the compiler loads each value
-// where it is first used; and a pointer to the table of the block's kind would turn the search
-// below into 16 dependent loads.
+// The three block-table rows of the block's group and the scalar fields at the end of the launch
+// arguments, all requested together at the kernel's start: one scalar round trip (the cache
+// behind the kernel arguments is cold at every launch) instead of one for the scalars, a
+// dependent one for the table of the block's kind and then the projection's record.  Left alone,
+// the compiler loads each value where it is first used; and a pointer to the table of the
+// block's kind would turn the search below into 16 dependent loads.
 typedef int i32x16 __attribute__((ext_vector_type(16)));
-static_assert(MAX_PROJ_PER_LAUNCH == 16, "the block tables are read as vectors of 16");
+static_assert(GROUP_PROJ == 16, "the block tables of a group are read as vectors of 16");
 struct LaunchTables {
     i32x16 shrink, pre, main;
+    int shrink_blocks, pre_base_blocks, group_blocks;
 };
-__device__ __forceinline__ LaunchTables pin_launch_args(const LayerArgs &a)
+__device__ __forceinline__ LaunchTables pin_launch_args(const LayerArgs &a, int z)
 {
     LaunchTables t;
-    t.shrink = *reinterpret_cast<const i32x16 *>(a.shrink_begin);
-    t.pre = *reinterpret_cast<const i32x16 *>(a.pre_begin);
-    t.main = *reinterpret_cast<const i32x16 *>(a.main_begin);
+    t.shrink = *reinterpret_cast<const i32x16 *>(a.shrink_begin[z]);
+    t.pre = *reinterpret_cast<const i32x16 *>(a.pre_begin[z]);
+    t.main = *reinterpret_cast<const i32x16 *>(a.main_begin[z]);
+    t.shrink_blocks = a.shrink_blocks[z];
+    t.pre_base_blocks = a.pre_base_blocks[z];
+    t.group_blocks = a.group_blocks[z];
     asm volatile("" :: "s"(t.shrink), "s"(t.pre), "s"(t.main), "s"(a.row_adapter), "s"(a.M), "s"(a.y_fp32),
-                       "s"(a.m_pad), "s"(a.shrink_blocks), "s"(a.pre_base_blocks), "s"(a.ctrl), "s"(a.status),
-                       "s"(a.code_mask), "s"(a.code_bias));
+                       "s"(a.m_pad), "s"(t.shrink_blocks), "s"(t.pre_base_blocks), "s"(t.group_blocks),
+                       "s"(a.ctrl), "s"(a.status), "s"(a.code_mask), "s"(a.code_bias), "s"(a.spin_limit));
     return t;
 }
 
@@ -1136,7 +1127,7 @@ __device__ __forceinline__ int find_proj(const i32x16 &begin, int b, int &first)
     int pi = 0;
     first = begin[0];
 #pragma unroll
-    for (int i = 1; i < MAX_PROJ_PER_LAUNCH; ++i) {
+    for (int i = 1; i < GROUP_PROJ; ++i) {
         pi += (b >= begin[i]) ? 1 : 0;
         first = (b >= begin[i]) ? begin[i] : first;
     }
@@ -1150,12 +1141,14 @@ template <int MB, int XR>
 __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) void layer_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
-    const LaunchTables tables = pin_launch_args(a);
+    const int z = (int)blockIdx.z;
+    const LaunchTables tables = pin_launch_args(a, z);
     const int b = (int)blockIdx.x;
+    if (b >= tables.group_blocks) return;                  // (the slices are as long as the longest group)
     int first;
-    if (b < a.shrink_blocks) {
+    if (b < tables.shrink_blocks) {
         if (blockIdx.y != 0) return;
-        const int pi = find_proj(tables.shrink, b, first);
+        const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
         // (the instances with one block of 16 rows are the ones launched for M <= 16)
         if constexpr (MB == 1) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
         else                   shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
@@ -1165,9 +1158,9 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     const int m0 = (int)blockIdx.y * 16 * MB;
     // (one call site for both kinds of base block: the kernel's code is large, and what runs
     // once per launch is paid for by instruction fetch)
-    const bool pre = b < a.shrink_blocks + a.pre_base_blocks;
-    const int bb = b - a.shrink_blocks - (pre ? 0 : a.pre_base_blocks);
-    const int pi = find_proj(pre ? tables.pre : tables.main, bb, first);
+    const bool pre = b < tables.shrink_blocks + tables.pre_base_blocks;
+    const int bb = b - tables.shrink_blocks - (pre ? 0 : tables.pre_base_blocks);
+    const int pi = z * GROUP_PROJ + find_proj(pre ? tables.pre : tables.main, bb, first);
     const ProjArgs P = fetch_proj(a, pi);
     const int local = bb - first;
     const int tiles = tiles_n(P.N);
@@ -1341,8 +1334,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     const u32x4 *wp = reinterpret_cast<const u32x4 *>(P.codes + (size_t)tile * ksteps * 64) + (size_t)unit_beg * 256;
     const uint2 *sp = P.scales + ((size_t)tile * (ksteps / SPG) + (size_t)unit_beg * gs) * 16;
 
-    [[maybe_unused]] const int trace_slot = (int)blockIdx.x * 4 + wave + (int)blockIdx.y * (int)gridDim.x * 4;
-    MLORA_TRACE_POINT(trace_slot, 0);
     // Every K unit of a tile takes a share of the LoRA term (the adapters of the chunk are dealt
     // out to the units in turn): the rows of B of many adapters are more than the finishing
     // blocks alone can fetch in good time.  So every unit waits for the shrink blocks, and
@@ -1391,7 +1382,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     auto math = [&](const WideRegs &r, int stage) {
         wide_math<SPG>(acc, prev, r, xfrag + stage * (L::X_STAGE / 16), mask, bias);
     };
-    MLORA_TRACE_POINT(trace_slot, 7);
 #pragma nounroll
     for (int ss = 0; ss < unit_cnt; ss += 2) {
         // stage ss: set A, x buffer 0
@@ -1414,7 +1404,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + xdst[i]) = xr[i];
     }
-    MLORA_TRACE_POINT(trace_slot, 2);
 
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -1511,11 +1500,15 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     }
 
     // element (mb, j, e) of this lane: row 16*mb + 4*lq + e of the chunk, column 16*j + l16 of the tile
-    if (tile_ok && need_s && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
+    // (a wave whose wait runs out sets the status word and stores NaN in place of its outputs)
+    bool poisoned = false;
+    if (tile_ok && need_s && !wait_count(sctr, (unsigned)P.n_shrink_blocks, a.spin_limit)) {
+        poisoned = true;
+        if (lane == 0) atomicOr(a.status, 1u);
+    }
     if (lora) {                                            // (uniform over the block)
         // a spare wave has not looked at the shrink counter: it must, before it reads t
-
-        if (!tile_ok && !wait_count(sctr, (unsigned)P.n_shrink_blocks) && lane == 0) atomicOr(a.status, 1u);
+        if (!tile_ok && !wait_count(sctr, (unsigned)P.n_shrink_blocks, a.spin_limit) && lane == 0) atomicOr(a.status, 1u);
         __syncthreads();                                   // every wave is done with the x buffers
         float *tl = reinterpret_cast<float *>(lds.buf);
         // t = alpha * sum over the K chunks of the shrink partials, in fixed order.  A thread takes
@@ -1557,7 +1550,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             }
         }
         __syncthreads();
-        MLORA_TRACE_POINT(trace_slot, 3);
         if (tile_ok) {
             auto compute = [&](const u32x4 (&bf)[4][4], const Round &r) {
 #pragma unroll
@@ -1600,7 +1592,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             }
         }
     }
-    MLORA_TRACE_POINT(trace_slot, 4);
     if (ku > 0) {
         // A partial tile (64 rows x 64 columns) lies in the workspace in the order of the MFMA
         // results, block (mb, j) of lane l at ((mb * 4 + j) * 64 + l) * 4: producer and consumer
@@ -1611,11 +1602,15 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) store_shared16(dst + (mb * 4 + j) * 256, acc[mb][j]);
+            compiler_fence();
             __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's stores have completed
             if (lane == 0) atomicAdd(pctr, 1u);
         }
     } else if (tile_ok && need_p) {
-        if (!wait_count(pctr, (unsigned)(P.ksplit - 1)) && lane == 0) atomicOr(a.status, 1u);
+        if (!wait_count(pctr, (unsigned)(P.ksplit - 1), a.spin_limit)) {
+            poisoned = true;
+            if (lane == 0) atomicOr(a.status, 1u);
+        }
         for (int u = 0; u + 1 < P.ksplit; ++u) {
             const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
             f32x4_t pv[16];
@@ -1628,7 +1623,12 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                 for (int j = 0; j < 4; ++j) acc[mb][j] += pv[mb * 4 + j];
         }
     }
-    MLORA_TRACE_POINT(trace_slot, 8);
+    if (poisoned) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{1.f, 1.f, 1.f, 1.f} * __uint_as_float(0x7FC00000u);
+    }
     if (tile_ok && ku == 0) {
         const bool full = tile * TILE_N + TILE_N <= N;
         if (full) {
@@ -1685,7 +1685,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                 }
         }
     }
-    MLORA_TRACE_POINT(trace_slot, 5);
 
     // counters back to zero for the next call (every wave owns the counters of its tile)
     if (tile_ok && lane == 0) {
@@ -1709,54 +1708,56 @@ template <int SPG>
 __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[wide_lds_bytes()];
-    const LaunchTables tables = pin_launch_args(a);
+    const int z = (int)blockIdx.z;
+    const LaunchTables tables = pin_launch_args(a, z);
     const int b = (int)blockIdx.x;
+    if (b >= tables.group_blocks) return;
     int first;
-    if (b < a.shrink_blocks) {
+    if (b < tables.shrink_blocks) {
         if (blockIdx.y != 0) return;
-        const int pi = find_proj(tables.shrink, b, first);
+        const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
         shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     WideLds &lds = *reinterpret_cast<WideLds *>(smem);
     const int m0 = (int)blockIdx.y * WIDE_ROWS;
-    if (b < a.shrink_blocks + a.pre_base_blocks) {
-        const int pb = b - a.shrink_blocks;
-        const int pi = find_proj(tables.pre, pb, first);
+    if (b < tables.shrink_blocks + tables.pre_base_blocks) {
+        const int pb = b - tables.shrink_blocks;
+        const int pi = z * GROUP_PROJ + find_proj(tables.pre, pb, first);
         const ProjArgs P = fetch_proj(a, pi);
         const int local = pb - first;
         const int groups = (tiles_n(P.N) + WIDE_TILES - 1) / WIDE_TILES;
         wide_unit<SPG>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
     } else {
-        const int mb_ = b - a.shrink_blocks - a.pre_base_blocks;
-        const int pi = find_proj(tables.main, mb_, first);
+        const int mb_ = b - tables.shrink_blocks - tables.pre_base_blocks;
+        const int pi = z * GROUP_PROJ + find_proj(tables.main, mb_, first);
         const ProjArgs P = fetch_proj(a, pi);
         wide_unit<SPG>(a, P, pi, mb_ - first, 0, m0, lds);
     }
 }
 
 template <int MB, int XR>
-static hipError_t launch_instance(const LayerArgs &a, int n_blocks, hipStream_t s)
+static hipError_t launch_instance(const LayerArgs &a, const dim3 &grid, hipStream_t s)
 {
-    const dim3 grid((unsigned)n_blocks, (unsigned)(a.m_pad / rows_per_chunk(a.M)));
     layer_kernel<MB, XR><<<grid, dim3(64 * Shape<MB>::WAVES), 0, s>>>(a);
     return hipGetLastError();
 }
 
-hipError_t launch_layer(const LayerArgs &a, int n_blocks, hipStream_t s)
+// grid: x = the longest group's blocks, y = row chunks, z = groups of up to 16 projections
+hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s)
 {
+    const dim3 grid((unsigned)grid_x, (unsigned)(a.m_pad / rows_per_chunk(a.M)), (unsigned)groups);
     if (a.M >= WIDE_MIN_ROWS) {
-        const dim3 grid((unsigned)n_blocks, (unsigned)(a.m_pad / rows_per_chunk(a.M)));
         // (the host puts only projections with the same group size into one wide launch)
         if (a.p[0].spg == 1)      wide_kernel<1><<<grid, dim3(256), 0, s>>>(a);
         else if (a.p[0].spg == 2) wide_kernel<2><<<grid, dim3(256), 0, s>>>(a);
         else                      wide_kernel<4><<<grid, dim3(256), 0, s>>>(a);
         return hipGetLastError();
     }
-    if (a.M <= 8)  return launch_instance<1, 8>(a, n_blocks, s);
-    if (a.M <= 16) return launch_instance<1, 16>(a, n_blocks, s);
-    if (a.M <= 24) return launch_instance<2, 24>(a, n_blocks, s);
-    return launch_instance<2, 32>(a, n_blocks, s);
+    if (a.M <= 8)  return launch_instance<1, 8>(a, grid, s);
+    if (a.M <= 16) return launch_instance<1, 16>(a, grid, s);
+    if (a.M <= 24) return launch_instance<2, 24>(a, grid, s);
+    return launch_instance<2, 32>(a, grid, s);
 }
 
 __global__ void zero_kernel(uint4 *p, size_t n)

@@ -34,18 +34,20 @@ def random_problem(seed, K, N, G, r, n_ad):
 
 
 def control_bytes(shapes, M):
-    """Size of the status word + completion counters at the head of a workspace (one launch of
-    up to 16 projections): 16 x 16 counter lines of 128 bytes and one more per (column tile, row
-    chunk) of every projection whose K is cut into more than one unit of 2048 inputs."""
-    rpc = 16 if M <= 16 else 32 if M < 64 else 64
+    """Size of the status word + completion counters at the head of a workspace (one launch):
+    16 counter lines of 128 bytes per projection and one more per (column tile, row chunk) of
+    every projection whose K is cut into more than one unit of 2048 inputs."""
+    rpc = 16 if M <= 16 else 32 if M < 33 else 64
     chunks = -(-M // rpc)
     n = sum(-(-s.N // 64) * chunks for s in shapes if -(-(s.K // 128) // 16) > 1)
-    return 256 + (16 * 16 + n) * 128
+    return 256 + (16 * len(shapes) + n) * 128
 
 
-def assert_workspace_clean(ws, shapes, M):
+def assert_workspace_clean(gpu, ws, shapes, M):
     """After a call the status word is 0 (no block gave up waiting) and every counter is back
     at 0, so the next call can use the workspace as it is."""
+    lib = gpu[0]
+    assert lib.workspace_status(ws) == 0, "a block gave up waiting"
     n = min(control_bytes(shapes, M), ws.numel())
     assert int(ws[:n].count_nonzero().item()) == 0, "status word or completion counters not zero"
 
@@ -61,7 +63,7 @@ def run_linear(gpu, prob, x_bits, rows, y_dtype):
     lib.linear(proj, x, ra, M, y, y_dtype, ws)
     torch.cuda.synchronize()
     if M > 0:
-        assert_workspace_clean(ws, [prob.shape], M)
+        assert_workspace_clean(gpu, ws, [prob.shape], M)
     return device.y_to_numpy(y)
 
 
@@ -288,7 +290,7 @@ def layer_on_gpu(gpu, probs, xs, rows, y_dtype):
     ws = device.alloc_workspace(projs, M)
     lib.layer_step(projs, dxs, ys, ra, M, y_dtype, ws)
     torch.cuda.synchronize()
-    assert_workspace_clean(ws, [p.shape for p in probs], M)
+    assert_workspace_clean(gpu, ws, [p.shape for p in probs], M)
     return [device.y_to_numpy(y) for y in ys]
 
 
@@ -352,7 +354,7 @@ def test_workspace_reuse_and_graph_replay_match_first_call(gpu):
 
     def snapshot_and_clobber():
         torch.cuda.synchronize()
-        assert_workspace_clean(ws, [p.shape for p in probs], M)
+        assert_workspace_clean(gpu, ws, [p.shape for p in probs], M)
         out = [y.clone() for y in ys]
         for y in ys:
             y.fill_(-1)

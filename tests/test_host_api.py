@@ -49,33 +49,45 @@ def proj(K=256, N=64, group=32, blob=0x1000, n_ad=2, rank=8, a=0x2000, b=0x3000,
 
 
 def test_workspace_bytes():
+    """Size = 256 (status header) + 2 * max(counters, data), each rounded up to 256 bytes: the
+    counters grow from the front, the data sits against the end, and with this size no call's
+    counters can meet another call's data in a workspace that fits both."""
     cdll = lib.load_library()
-    # 256 B status header + completion counters whenever blocks hand data to each other: 16
-    # projections x 16 copies of the shrink counters, each in a 128-byte line of its own
-    ctl = 256 + 16 * 16 * 128
+
+    def need(ctrl, data):
+        r = lambda v: (v + 255) // 256 * 256
+        return 256 + 2 * max(r(ctrl), r(data))
+
+    lines = lambda n_proj, part: (16 * n_proj + part) * 128    # 16 copies of a shrink counter per projection
     p = proj(K=2048, rank=16)
     # K/1024 = 2 chunks (at most 16) x M x rank16 x 4 bytes, rounded up to 256
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == ctl + 2 * 8 * 16 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == need(lines(1, 0), 2 * 8 * 16 * 4)
     p = proj(K=256, rank=8)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == ctl + 256
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 3) == need(lines(1, 0), 256)
     # K = 16384 = 8 units of 2048 inputs: 7 fp32 partial tiles [m_pad = 64][64] per tile of columns
     p = proj(K=16384, rank=64)
     # (+ one counter line per (tile, row chunk) of a split-K projection: 1 tile x 1 chunk)
     # (33 rows and more, chunks of 64 rows: a launch this small is cut further, here into 32
     # units of 4 x 128 inputs; the shrink step leaves 16 chunks of partial sums)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == ctl + 1 * 128 + 16 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == ctl + 1 * 128 + 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == need(lines(1, 1), 16 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == need(lines(1, 1), 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
     # (17 to 32 rows: one chunk of 32 rows, 8 units of 2048 inputs)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == ctl + 1 * 128 + 16 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == need(lines(1, 1), 16 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4)
     # a launch of the 64-row kernel with 80 to 240 base blocks gets K units of 8 x 128 inputs:
     # K = 3072, N = 8192 (128 tiles = 32 blocks of columns), 128 rows (2 chunks) -> 3 units
     p = proj(K=3072, N=8192, group=64, rank=16)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 128) == (ctl + 128 * 2 * 128 + 3 * 128 * 16 * 4
-                                                                + 2 * 128 * 128 * 64 * 4)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 128) == need(lines(1, 128 * 2), 3 * 128 * 16 * 4
+                                                                     + 2 * 128 * 128 * 64 * 4)
     p = proj(K=4096, N=200, n_ad=0, rank=0, a=None, b=None)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == ctl + 4 * 128 + 1 * 4 * 16 * 64 * 4
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 5) == need(lines(1, 4), 1 * 4 * 16 * 64 * 4)
     p = proj(n_ad=0, rank=0, a=None, b=None)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 8) == 0
+    # several projections in one launch: 16 counter lines each
+    arr = (binding._ProjStruct * 3)(proj(K=2048, rank=16), proj(K=256, rank=8), proj(K=2048, rank=16))
+    assert cdll.mlora_w4_workspace_bytes(arr, 3, 8) == need(lines(3, 0), 2 * (2 * 8 * 16 * 4) + 256)
+    # unsupported shapes and row counts have no size
+    assert cdll.mlora_w4_workspace_bytes(C.byref(proj(K=100)), 1, 8) == 0
+    assert cdll.mlora_w4_workspace_bytes(C.byref(proj()), 1, 4097) == 0
 
 
 def test_workspace_init_rejects_bad_arguments():
@@ -92,6 +104,9 @@ def call_linear(p, x=0x4000, rows=0x5000, M=4, y=0x6000, y_dtype=0, ws=0x7000, w
 def test_linear_rejects_bad_arguments_before_launch():
     assert call_linear(proj(K=100)) == ESHAPE
     assert call_linear(proj(K=192)) == ESHAPE                 # K % 128
+    for K in (32, 64, 96):                                     # multiples of the MFMA step, not of 128
+        assert call_linear(proj(K=K)) == ESHAPE
+        assert lib.blob_bytes(K, 64, 32) == 0
     assert call_linear(proj(group=48)) == ESHAPE
     assert call_linear(proj(N=0)) == ESHAPE
     assert call_linear(proj(rank=12)) == ESHAPE
@@ -123,6 +138,28 @@ def test_layer_step_rejects_shared_outputs_and_bad_counts():
     ys = (C.c_void_p * 2)(0x6000, 0x8000)
     assert cdll.mlora_w4_layer_step(arr, 0, xs, ys, 0x5000, 4, 0, 0x7000, 1 << 20, None) == EINVAL
     assert cdll.mlora_w4_layer_step(arr, 2, None, ys, 0x5000, 4, 0, 0x7000, 1 << 20, None) == EINVAL
+
+
+def test_index_range_guard_refuses_the_whole_call_before_any_launch():
+    """A projection with 2^16 column tiles is beyond the exact range of the kernels' block-index
+    division.  It sits in the SECOND launch of the call (after 128 ordinary projections): the
+    call is refused as a whole on the host, nothing is enqueued (all pointers here are fake)."""
+    cdll = lib.load_library()
+    n = 130
+    arr = (binding._ProjStruct * n)(*[proj() for _ in range(n)])
+    arr[129] = proj(N=1 << 22)
+    xs = (C.c_void_p * n)(*[0x4000] * n)
+    ys = (C.c_void_p * n)(*[0x100000 + 0x1000 * i for i in range(n)])
+    assert cdll.mlora_w4_layer_step(arr, n, xs, ys, 0x5000, 4, 0, 0x7000, 1 << 40, None) == ESHAPE
+    assert cdll.mlora_w4_workspace_bytes(arr, n, 4) == 0
+
+
+def test_workspace_status_and_spin_limit_hooks():
+    cdll = lib.load_library()
+    assert cdll.mlora_w4_workspace_status(None, None, None) == EINVAL
+    old = lib.debug_spin_limit(7)
+    assert lib.debug_spin_limit(-1) == 7                      # negative: back to the default
+    assert lib.debug_spin_limit(old) == old
 
 
 def test_prepack_unpack_group_rows_reject_bad_arguments():
