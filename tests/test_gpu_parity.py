@@ -7,64 +7,10 @@ import pytest
 
 import oracle
 import workloads as wl
+from gpu_util import (TOL, TOL_F32, assert_workspace_clean, check_linear, layer_on_gpu,
+                      random_problem, rel_err, run_linear)
 
 pytestmark = pytest.mark.gpu
-
-TOL = 5e-3        # the stated gate, bf16 output (output rounding alone can reach 2^-8 = 3.9e-3)
-TOL_F32 = 2e-4    # fp32 output: only fp32 accumulation-order error remains (observed ~1e-6)
-
-
-@pytest.fixture(scope="module")
-def gpu():
-    import torch
-    assert torch.cuda.is_available(), "needs a GPU"
-    import paper_2604_18655_amd as lib
-    from paper_2604_18655_amd import device
-    lib.load_library()
-    return lib, device, torch
-
-
-def rel_err(y, ref):
-    return float(np.max(np.abs(y - ref)) / np.max(np.abs(ref)))
-
-
-def random_problem(seed, K, N, G, r, n_ad):
-    shape = wl.ProjShape("t", K, N, G, r, n_ad, 2.0)
-    return wl.make_problem(shape, 900 + seed, 0, 0)
-
-
-def control_bytes(shapes, M):
-    """Size of the status word + completion counters at the head of a workspace (one launch):
-    16 counter lines of 128 bytes per projection and one more per (column tile, row chunk) of
-    every projection whose K is cut into more than one unit of 2048 inputs."""
-    rpc = 16 if M <= 16 else 32 if M < 33 else 64
-    chunks = -(-M // rpc)
-    n = sum(-(-s.N // 64) * chunks for s in shapes if -(-(s.K // 128) // 16) > 1)
-    return 256 + (16 * len(shapes) + n) * 128
-
-
-def assert_workspace_clean(gpu, ws, shapes, M):
-    """After a call the status word is 0 (no block gave up waiting) and every counter is back
-    at 0, so the next call can use the workspace as it is."""
-    lib = gpu[0]
-    assert lib.workspace_status(ws) == 0, "a block gave up waiting"
-    n = min(control_bytes(shapes, M), ws.numel())
-    assert int(ws[:n].count_nonzero().item()) == 0, "status word or completion counters not zero"
-
-
-def run_linear(gpu, prob, x_bits, rows, y_dtype):
-    lib, device, torch = gpu
-    proj = device.upload_problem(prob)
-    M = x_bits.shape[0]
-    x = device.to_device(x_bits)
-    ra = None if rows is None else torch.from_numpy(np.ascontiguousarray(rows, np.int32)).cuda()
-    y = device.alloc_y(M, prob.shape.N, y_dtype)
-    ws = device.alloc_workspace([proj], max(M, 1))
-    lib.linear(proj, x, ra, M, y, y_dtype, ws)
-    torch.cuda.synchronize()
-    if M > 0:
-        assert_workspace_clean(gpu, ws, [prob.shape], M)
-    return device.y_to_numpy(y)
 
 
 # ------------------------------------------------------------------------------ unpack
@@ -136,25 +82,6 @@ def test_group_rows_flags_out_of_range_index(gpu):
 
 
 # ------------------------------------------------------------------------------ linear
-
-def check_linear(gpu, prob, x_bits, rows, tag):
-    G, alpha = prob.shape.group, prob.shape.alpha
-    ref = oracle.linear(prob.wq, prob.scales, G, prob.lora_a, prob.lora_b, alpha, x_bits, rows)
-    base = oracle.linear(prob.wq, prob.scales, G, prob.lora_a, prob.lora_b, alpha, x_bits, None)
-    y16 = run_linear(gpu, prob, x_bits, rows, 0)
-    y32 = run_linear(gpu, prob, x_bits, rows, 1)
-    yb32 = run_linear(gpu, prob, x_bits, None, 1)
-    e16, e32 = rel_err(y16, ref), rel_err(y32, ref)
-    print(f"{tag}: bf16-out err {e16:.2e}  fp32-out err {e32:.2e}", flush=True)
-    assert e16 <= TOL, tag
-    assert e32 <= TOL_F32, tag
-    assert rel_err(yb32, base) <= TOL_F32, tag
-    delta_ref = ref - base
-    if np.max(np.abs(delta_ref)) > 0:
-        # the LoRA term on its own scale: a wrong adapter or a dropped alpha fails here
-        assert float(np.max(np.abs((y32 - yb32) - delta_ref)) / np.max(np.abs(delta_ref))) <= TOL, tag
-    return y16
-
 
 def test_config1_tiny(gpu):
     w = wl.WORKLOADS["c1"]
@@ -275,25 +202,6 @@ def test_rows_sharing_an_adapter_match_single_row_calls(gpu):
         assert rel_err(y1[0:1], y[m:m + 1]) <= 1e-5
 
 
-def layer_on_gpu(gpu, probs, xs, rows, y_dtype):
-    lib, device, torch = gpu
-    projs = [device.upload_problem(p) for p in probs]
-    cache = {}
-    dxs = []
-    for x in xs:
-        if id(x) not in cache:
-            cache[id(x)] = device.to_device(x)
-        dxs.append(cache[id(x)])
-    M = xs[0].shape[0]
-    ra = torch.from_numpy(rows).cuda()
-    ys = [device.alloc_y(M, p.shape.N, y_dtype) for p in probs]
-    ws = device.alloc_workspace(projs, M)
-    lib.layer_step(projs, dxs, ys, ra, M, y_dtype, ws)
-    torch.cuda.synchronize()
-    assert_workspace_clean(gpu, ws, [p.shape for p in probs], M)
-    return [device.y_to_numpy(y) for y in ys]
-
-
 @pytest.mark.parametrize("M", [5, 40, 72])
 def test_layer_step_many_projections_mixed_groups(gpu, M):
     """More projections than one launch holds (16), group sizes mixed (33 rows and more: a launch
@@ -381,58 +289,3 @@ def test_workspace_reuse_and_graph_replay_match_first_call(gpu):
         plan.run()                                   # eager work between replays
         again = snapshot_and_clobber()
         assert all(torch.equal(a, b) for a, b in zip(first, again))
-
-
-def test_config2_layer_step_all_projections(gpu):
-    w = wl.WORKLOADS["c2"]
-    probs, xs, rows = wl.make_layer(w)
-    ys = layer_on_gpu(gpu, probs, xs, rows, 0)
-    ys32 = layer_on_gpu(gpu, probs, xs, rows, 1)
-    for p, x, y, y32 in zip(probs, xs, ys, ys32):
-        ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows)
-        print(f"c2 {p.shape.name}: {rel_err(y, ref):.2e} / {rel_err(y32, ref):.2e}", flush=True)
-        assert rel_err(y, ref) <= TOL and rel_err(y32, ref) <= TOL_F32
-
-
-@pytest.mark.parametrize("key", ["c3", "c3_interleaved"])
-def test_config3_tree_rows(gpu, key):
-    w = wl.WORKLOADS[key]
-    probs, xs, rows = wl.make_layer(w)
-    check_linear(gpu, probs[0], xs[0], rows, key)
-
-
-@pytest.mark.parametrize("key", ["c5_up", "c5_down"])
-def test_config5_zipf(gpu, key):
-    # full-size weights; the oracle is evaluated on a sample of 512 output columns
-    w = wl.WORKLOADS[key]
-    probs, xs, rows = wl.make_layer(w)
-    p = probs[0]
-    y32 = run_linear(gpu, p, xs[0], rows, 1)
-    y16 = run_linear(gpu, p, xs[0], rows, 0)
-    cols = np.sort(np.random.default_rng(9).choice(p.shape.N, size=512, replace=False))
-    cols[0], cols[-1] = 0, p.shape.N - 1
-    ref = oracle.linear(p.wq[cols], p.scales[cols], p.shape.group, p.lora_a,
-                        np.ascontiguousarray(p.lora_b[:, cols, :]), p.shape.alpha, xs[0], rows)
-    print(f"{key}: {rel_err(y16[:, cols], ref):.2e} / {rel_err(y32[:, cols], ref):.2e}", flush=True)
-    assert rel_err(y16[:, cols], ref) <= TOL and rel_err(y32[:, cols], ref) <= TOL_F32
-
-
-@pytest.mark.parametrize("key", ["c4_decode", "c4_prefill"])
-def test_config4_one_layer_sampled(gpu, key):
-    # layer 3 of the 16-layer stack at full size; oracle on 96 sampled columns per projection
-    # (and, for the 512-row prefill chunk, on 48 sampled rows)
-    w = wl.WORKLOADS[key]
-    probs, xs, rows = wl.make_layer(w, layer=3)
-    ys32 = layer_on_gpu(gpu, probs, xs, rows, 1)
-    ys16 = layer_on_gpu(gpu, probs, xs, rows, 0)
-    rng = np.random.default_rng(11)
-    msel = np.arange(w.M) if w.M <= 64 else np.sort(rng.choice(w.M, size=48, replace=False))
-    for p, x, y16, y32 in zip(probs, xs, ys16, ys32):
-        cols = np.sort(rng.choice(p.shape.N, size=96, replace=False))
-        ref = oracle.linear(p.wq[cols], p.scales[cols], p.shape.group, p.lora_a,
-                            np.ascontiguousarray(p.lora_b[:, cols, :]), p.shape.alpha,
-                            np.ascontiguousarray(x[msel]), np.ascontiguousarray(rows[msel]))
-        e16 = rel_err(y16[np.ix_(msel, cols)], ref)
-        e32 = rel_err(y32[np.ix_(msel, cols)], ref)
-        print(f"{key} {p.shape.name}: {e16:.2e} / {e32:.2e}", flush=True)
-        assert e16 <= TOL and e32 <= TOL_F32

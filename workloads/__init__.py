@@ -7,13 +7,13 @@ the CPU oracle nor the HIP library; both consume what it produces.
 """
 from .configs import (ProjShape, Workload, WORKLOADS, llama1b_layer_shapes,
                       ds2d_rows, algorithmic_bytes, algorithmic_flops)
-from .generate import (Problem, make_problem, make_layer, make_rows,
+from .generate import (Problem, make_problem, make_layer, make_layer_inputs, make_rows,
                        f32_to_bf16_bits, bf16_bits_to_f32, quantise_int4,
                        pack_nibbles)
 
 __all__ = [
     "ProjShape", "Workload", "WORKLOADS", "llama1b_layer_shapes", "ds2d_rows",
     "algorithmic_bytes", "algorithmic_flops", "Problem", "make_problem",
-    "make_layer", "make_rows", "f32_to_bf16_bits", "bf16_bits_to_f32",
+    "make_layer", "make_layer_inputs", "make_rows", "f32_to_bf16_bits", "bf16_bits_to_f32",
     "quantise_int4", "pack_nibbles",
 ]

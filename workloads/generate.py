@@ -116,13 +116,9 @@ def make_rows(row_map: str, M: int, n_adapters: int, cfg_id: int = 0) -> np.ndar
     return a.astype(np.int32)
 
 
-def make_layer(wl: Workload, layer: int = 0) -> Tuple[List[Problem], List[np.ndarray], np.ndarray]:
-    """All projections of one layer of a workload: (problems, xs, row_adapter).
-
-    xs[i] is the input of projection i; projections naming the same x_slot get
-    the very same array object (q/k/v and gate/up share their rows).
-    """
-    problems = [make_problem(s, wl.cfg_id, layer, i) for i, s in enumerate(wl.projs)]
+def make_layer_inputs(wl: Workload, layer: int = 0) -> Tuple[None, List[np.ndarray], np.ndarray]:
+    """The rows of one layer of a workload without its weights: (None, xs, row_adapter), the
+    same xs and rows that make_layer returns."""
     slots: Dict[Tuple[str, int], np.ndarray] = {}
     xs = []
     for s in wl.projs:
@@ -131,4 +127,15 @@ def make_layer(wl: Workload, layer: int = 0) -> Tuple[List[Problem], List[np.nda
             slots[key] = make_x(wl.M, s.K, wl.cfg_id, layer, len(slots))
         xs.append(slots[key])
     rows = make_rows(wl.row_map, wl.M, wl.projs[0].n_adapters, wl.cfg_id)
+    return None, xs, rows
+
+
+def make_layer(wl: Workload, layer: int = 0) -> Tuple[List[Problem], List[np.ndarray], np.ndarray]:
+    """All projections of one layer of a workload: (problems, xs, row_adapter).
+
+    xs[i] is the input of projection i; projections naming the same x_slot get
+    the very same array object (q/k/v and gate/up share their rows).
+    """
+    problems = [make_problem(s, wl.cfg_id, layer, i) for i, s in enumerate(wl.projs)]
+    _, xs, rows = make_layer_inputs(wl, layer)
     return problems, xs, rows
