@@ -54,7 +54,8 @@ enum { MLORA_Y_BF16 = 0, MLORA_Y_FP32 = 1 };
 enum {
     MLORA_MAX_ROWS = 4096,      /* M */
     MLORA_MAX_ADAPTERS = 1024,  /* n_adapters */
-    MLORA_MAX_RANK = 128        /* rank; must also be a multiple of 8 */
+    MLORA_MAX_RANK = 128,       /* rank; must also be a multiple of 8 */
+    MLORA_STATIC_SCRATCH_MIB = 32 /* size of the built-in scratch of mlora_w4_layer_step_static */
 };
 
 /* One projection.  K = input features, N = output features.
@@ -156,6 +157,24 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
                                  const void *const *xs, void *const *ys,
                                  const int32_t *row_adapter, int32_t M, int32_t y_dtype,
                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* mlora_w4_layer_step for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): no workspace argument.  What
+ * the kernels hand to each other lives in a scratch array inside the library's device image
+ * (MLORA_STATIC_SCRATCH_MIB MiB per GPU, held until the process ends).  The call allocates and
+ * frees nothing; it clears the status word and the counters it will use with a small fill
+ * kernel on `stream`, then enqueues the same kernels as mlora_w4_layer_step, so the results are
+ * bit-identical to that call's.
+ *  - MLORA_EWORKSPACE if the call needs more than the array holds (counters + data + 256 bytes,
+ *    without the doubling of mlora_w4_workspace_bytes): 112 projections of a 1B-like model at
+ *    32 rows need 14 MiB; a 512-row call over 16 such layers does not fit.
+ *  - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *    streams, two threads) race, as two calls on one workspace would.  The array keeps the last
+ *    call's contents between calls. */
+mlora_status mlora_w4_layer_step_static(const mlora_w4_proj *projs, int32_t n_proj,
+                                        const void *const *xs, void *const *ys,
+                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                        void *stream);
 
 const char *mlora_strerror(mlora_status status);
 

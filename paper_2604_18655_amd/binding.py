@@ -16,6 +16,7 @@ exported_symbols = (
     "mlora_strerror", "mlora_w4_blob_bytes", "mlora_w4_prepack", "mlora_w4_unpack",
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
     "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
+    "mlora_w4_layer_step_static",
 )
 
 
@@ -62,6 +63,8 @@ def load_library():
         lib.mlora_w4_layer_step.restype = C.c_int
         lib.mlora_w4_layer_step.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32, i32,
                                             vp, sz, vp]
+        lib.mlora_w4_layer_step_static.restype = C.c_int
+        lib.mlora_w4_layer_step_static.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32, i32, vp]
         lib.mlora_w4_workspace_init.restype = C.c_int
         lib.mlora_w4_workspace_init.argtypes = [vp, sz, vp]
         lib.mlora_w4_workspace_status.restype = C.c_int
@@ -192,6 +195,19 @@ class LayerPlan:
                      self.ws, self.ws_bytes, _stream() if stream is None else stream)
         if st != 0:
             raise MloraError(st, "mlora_w4_layer_step")
+
+
+def layer_step_static(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,
+                      y_dtype: int = Y_BF16) -> None:
+    """mlora_w4_layer_step_static: the library's built-in scratch instead of a workspace."""
+    n = len(projs)
+    assert n == len(xs) == len(ys)
+    arr = _proj_array(projs)
+    cxs = (C.c_void_p * n)(*[_ptr(x) for x in xs])
+    cys = (C.c_void_p * n)(*[_ptr(y) for y in ys])
+    _check(load_library().mlora_w4_layer_step_static(arr, n, cxs, cys, _ptr(row_adapter), int(M),
+                                                     int(y_dtype), _stream()),
+           "mlora_w4_layer_step_static")
 
 
 def layer_step(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,

@@ -3,11 +3,40 @@
 
 #include <algorithm>
 #include <memory>
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
 
 using namespace mlora;
+
+// ---------------------------------------------------------------------------------------------
+// The same call on a scratch buffer that lives in the library's own device image, for callers
+// that cannot allocate.  Every device the library runs on holds its own copy of the array at
+// its own address; in host code the array's name is only a handle, so the device address is
+// looked up once per device (with that device current) and used from then on.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)MLORA_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static char *g_scratch_ptr[MAX_DEVICES];
+
+// device address of the current device's copy of `scratch` (null on error)
+static char *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = reinterpret_cast<char *>(ptr);
+    }
+    return g_scratch_ptr[dev];
+}
+
 
 namespace {
 
@@ -418,6 +447,34 @@ mlora_status mlora_w4_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
     return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
                         need > 0 ? reinterpret_cast<char *>(workspace) : nullptr, workspace_bytes, data_total,
                         (hipStream_t)stream);
+}
+
+mlora_status mlora_w4_layer_step_static(const mlora_w4_proj *projs, int32_t n_proj,
+                                        const void *const *xs, void *const *ys,
+                                        const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                        void *stream)
+{
+    mlora_status st = check_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype);
+    if (st != MLORA_OK) return st;
+    if (M == 0) return MLORA_OK;
+    size_t ctrl_total, data_total;
+    st = plan_call(projs, n_proj, M, true, ctrl_total, data_total);
+    if (st != MLORA_OK) return st;
+    // counters at the front, data against the end: the two must not meet
+    const size_t head = WS_HEADER_BYTES + round_up(ctrl_total, 256);
+    if (head + round_up(data_total, 256) > STATIC_SCRATCH_BYTES) return MLORA_EWORKSPACE;
+    char *ws = nullptr;
+    if (ctrl_total > 0) {
+        ws = static_scratch();
+        if (!ws) return MLORA_EHIP;
+        // The array keeps what the last call left: status word and counters start from zero again
+        // (a fill kernel, not a memset node: the call may be under stream capture).
+        if (launch_zero(ws, head, (hipStream_t)stream) != hipSuccess) return MLORA_EHIP;
+    }
+    bool any_lora = false;
+    for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
+    return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
+                        ws, STATIC_SCRATCH_BYTES, data_total, (hipStream_t)stream);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,
