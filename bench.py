@@ -1,15 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the multi-LoRA int4 layer step on one MI355X.
 
-A step is one pass of the whole hot path over one batch of synthetic rows: one
+A step is one pass of the whole hot path over one batch of synthetic rows: ONE
 mlora_w4_layer_step call over all projections of the workload (group rows, shrink, base
-product, expand).  Weights, adapters and rows are resident in HBM before the timed region;
-R independently seeded copies of all tensors are cycled so that R * bytes >= 3 x 256 MiB and
-every step streams its weights from HBM rather than from the last-level cache.
+product, expand) -- for the default workload, c4_decode, the 112 projections of a 16-layer
+stack at 32 rows, which the library runs as one launch.  Weights, adapters and rows are
+resident in HBM before the timed region; R independently seeded copies of all tensors are
+cycled so that R * bytes >= 3 x 256 MiB and every step streams its weights from HBM rather
+than from the last-level cache.
 
 Prints ONE JSON line: value = algorithmic bytes per step / time per step (GB/s), with the time
-per linear, the roofline block of the dominant kernel (HIP events around each of its launches)
-and the CPU oracle timed on the host cores as a reported baseline.
+per linear, the roofline block of the dominant kernel (HIP events around its launches), the
+same stack run in dependency order (q,k,v | o | gate,up | down: four calls per layer), the
+error of one layer against the CPU oracle, and the oracle timed on the host cores as a
+reported baseline.
 """
 from __future__ import annotations
 
@@ -17,6 +21,7 @@ import argparse
 import json
 import math
 import os
+import re
 import sys
 import time
 
@@ -28,29 +33,44 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0          # dense bf16, MI355X
 CACHE_BYTES = 256 << 20
 METRIC = "µs per multi-LoRA W4 linear + achieved HBM GB/s (% of 8 TB/s), 1 MI355X"
-
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by a copy kernel of known size; see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC = {"c2": 49030614}     # bytes per launch: profiles/layer_kernel_c2_hbm_traffic.txt
+# which roofline bounds a workload (the others are reported beside it)
+BOUND = {"c1": "hbm", "c2": "hbm", "c4_decode": "hbm", "c5_up": "hbm", "c5_down": "hbm",
+         "c3": "mfma", "c3_interleaved": "mfma", "c4_prefill": "mfma"}
+DEPENDENCY_ORDER = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c2", help="c2 (default), c1, c3, c4_decode, c4_prefill, c5_up, c5_down")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c4_decode",
+                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
                          "eager: one library call per step from Python")
     ap.add_argument("--copies", type=int, default=0, help="rotating copies (0 = enough to defeat the cache)")
+    ap.add_argument("--per-layer-calls", action="store_true",
+                    help="one library call (one launch) per layer instead of one per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dependency-order", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device-to-device copies of 256 MiB (torch clone): a kernel of "
                          "known traffic next to which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings "
                          "of the layer kernel can be scaled")
     ap.add_argument("--y-fp32", action="store_true")
     return ap.parse_args()
+
+
+def measured_traffic(kernel_tag: str, workload: str):
+    """HBM bytes per launch from the tracked rocprofv3 --pmc summary of this kernel and workload
+    (profiles/<kernel>_<workload>_hbm_traffic.txt, line 'hbm_traffic_bytes_per_launch = N'), or
+    None if no such summary is there."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    m = re.search(r"hbm_traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read())
+    return (int(m.group(1)), os.path.relpath(path, ROOT)) if m else (None, None)
 
 
 def main():
@@ -75,42 +95,62 @@ def main():
     y_dtype = lib.Y_FP32 if args.y_fp32 else lib.Y_BF16
     ysz = 4 if args.y_fp32 else 2
     M = w.M
+    n_proj = len(w.projs)
 
     rows0 = wl.make_rows(w.row_map, M, w.projs[0].n_adapters, w.cfg_id)
     U = len(set(int(a) for a in rows0 if a >= 0))
     layer_bytes = sum(wl.algorithmic_bytes(p, M, U, ysz) for p in w.projs)
     layer_flops = sum(wl.algorithmic_flops(p, M) for p in w.projs)
-
     step_bytes, step_flops = layer_bytes * w.layers, layer_flops * w.layers
 
     # rotating copies: each "copy" is a full set of w.layers layers
-    copies = args.copies or max(1, math.ceil(3 * CACHE_BYTES / step_bytes))
+    copies = args.copies or max(2 if w.layers > 1 else 1, math.ceil(3 * CACHE_BYTES / step_bytes))
     t0 = time.time()
-    plans, host_sets = [], []
+    sets = []                       # per copy: (projs, dxs, ys, ra) over all layers
+    host_layer0 = None
     for c in range(copies):
+        projs, dxs, ys = [], [], []
         for layer in range(w.layers):
             probs, xs, rows = wl.make_layer(w, layer=c * w.layers + layer)
-            projs = [device.upload_problem(p, dev) for p in probs]
-            cache, dxs = {}, []
+            projs += [device.upload_problem(p, dev) for p in probs]
+            cache = {}
             for x in xs:
                 if id(x) not in cache:
                     cache[id(x)] = device.to_device(x, dev)
                 dxs.append(cache[id(x)])
-            ra = torch.from_numpy(rows).to(dev)
-            ys = [device.alloc_y(M, p.shape.N, y_dtype, dev) for p in probs]
-            ws = device.alloc_workspace(projs, M, dev)
-            plans.append(lib.LayerPlan(projs, dxs, ys, ra, M, y_dtype, ws))
+            ys += [device.alloc_y(M, p.shape.N, y_dtype, dev) for p in probs]
             if c == 0 and layer == 0:
-                host_sets.append((probs, xs, rows))
+                host_layer0 = (probs, xs, rows)
+        ra = torch.from_numpy(rows).to(dev)
+        sets.append((projs, dxs, ys, ra))
+    # one workspace per copy, sized for the whole step: the calls of a step follow each other on
+    # one stream, and a workspace serves calls of any geometry one after another
+    plans, dep_plans, workspaces = [], [], []
+    for projs, dxs, ys, ra in sets:
+        ws = device.alloc_workspace(projs, M, dev)
+        workspaces.append(ws)
+        if args.per_layer_calls:
+            plans.append([lib.LayerPlan(projs[l * n_proj:(l + 1) * n_proj], dxs[l * n_proj:(l + 1) * n_proj],
+                                        ys[l * n_proj:(l + 1) * n_proj], ra, M, y_dtype, ws)
+                          for l in range(w.layers)])
+        else:
+            plans.append([lib.LayerPlan(projs, dxs, ys, ra, M, y_dtype, ws)])
+        names = [p.name for p in w.projs]
+        if n_proj == 7 and all(any(n in grp for grp in DEPENDENCY_ORDER) for n in names):
+            calls = []
+            for l in range(w.layers):
+                for grp in DEPENDENCY_ORDER:
+                    idx = [l * n_proj + names.index(n) for n in grp]
+                    calls.append(lib.LayerPlan([projs[i] for i in idx], [dxs[i] for i in idx],
+                                               [ys[i] for i in idx], ra, M, y_dtype, ws))
+            dep_plans.append(calls)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
-    calls_per_step = w.layers
-    n_plans = len(plans)
+    calls_per_step = len(plans[0])
 
-    def run_step(i, stream=None):
-        base = (i % copies) * calls_per_step
-        for l in range(calls_per_step):
-            plans[base + l].run(stream)
+    def run_step(i, stream=None, table=plans):
+        for plan in table[i % copies]:
+            plan.run(stream)
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -120,55 +160,75 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- warm-up, then the timed region: exactly K steps between two synchronisations
-    for i in range(args.warmup):
-        run_step(i)
-    torch.cuda.synchronize()
+    def timed(table, K, warmup):
+        """Exactly K steps between two synchronisations (wall clock), and the same region between
+        two HIP events recorded on the stream the launches go to."""
+        for i in range(warmup):
+            run_step(i, None, table)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if args.mode == "graph":
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    for i in range(K):
+                        run_step(warmup + i, side.cuda_stream, table)
+            torch.cuda.current_stream().wait_stream(side)
+            graph.replay()                    # untimed: the first replay uploads the graph
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            ev0.record()
+            graph.replay()
+            ev1.record()
+            torch.cuda.synchronize()
+            elapsed = time.perf_counter() - t_start
+        else:
+            t_start = time.perf_counter()
+            ev0.record()
+            for i in range(K):
+                run_step(warmup + i, None, table)
+            ev1.record()
+            torch.cuda.synchronize()
+            elapsed = time.perf_counter() - t_start
+        return elapsed, ev0.elapsed_time(ev1) * 1e-3
 
     K = args.steps
-    # The timed region: exactly K steps between two synchronisations (wall clock), and the same
-    # region between two HIP events recorded on the stream the launches go to, which gives the
-    # average duration of the one kernel a layer call launches (launch gap included).
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    if args.mode == "graph":
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(K):
-                    run_step(args.warmup + i, side.cuda_stream)
-        torch.cuda.current_stream().wait_stream(side)
-        graph.replay()                    # untimed: first replay uploads the graph
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        ev0.record()
-        graph.replay()
-        ev1.record()
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t_start
-    else:
-        t_start = time.perf_counter()
-        ev0.record()
-        for i in range(K):
-            run_step(args.warmup + i)
-        ev1.record()
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t_start
+    elapsed, ev_s = timed(plans, K, args.warmup)
     ms_per_step = elapsed * 1e3 / K
     gbs = step_bytes / (elapsed / K) / 1e9
 
-    # ---- the dominant (only) kernel: one launch per 16 projections of a layer call
-    launches_per_step = calls_per_step * math.ceil(len(w.projs) / 16)
+    # ---- after the timed region: no block gave up waiting, and the outputs are right
+    for ws in workspaces:
+        assert lib.workspace_status(ws) == 0, "a block gave up waiting for another: results invalid"
+    import oracle
+    probs0, xs0, rows_h = host_layer0
+    max_rel_err = 0.0
+    sample = list(range(n_proj)) if M <= 64 else [0, n_proj - 1]
+    msel = np.arange(M) if M <= 64 else np.unique(np.concatenate([[0, M - 1], np.arange(0, M, 37)]))
+    for i in sample:
+        p = probs0[i]
+        ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
+                            np.ascontiguousarray(xs0[i][msel]), np.ascontiguousarray(rows_h[msel]))
+        got = device.y_to_numpy(sets[0][2][i])[msel]
+        max_rel_err = max(max_rel_err, float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))))
+    assert max_rel_err <= (2e-4 if args.y_fp32 else 5e-3), max_rel_err
+
+    # ---- the dominant (only) kernel: one launch per call
+    launches_per_step = calls_per_step * math.ceil((n_proj * w.layers // calls_per_step) / 128)
     n_ev = K * launches_per_step
-    kern_ms = ev0.elapsed_time(ev1) / n_ev
+    kern_s = ev_s / n_ev
     base_bytes = step_bytes / launches_per_step
-    achieved = base_bytes / (kern_ms * 1e-3) / 1e9
-    wide = M >= 33                       # the library's kernel for 33 rows and more: bounded by the matrix units
+    achieved = base_bytes / kern_s / 1e9
+    wide = M >= 33                       # the library's kernel for 33 rows and more
     spg = w.projs[0].group // 32
     kernel_name = ("wide_kernel<%d>" % spg) if wide else \
         "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
-    achieved_tflops = (step_flops / launches_per_step) / (kern_ms * 1e-3) / 1e12
+    kernel_tag = "wide_kernel" if wide else "layer_kernel"
+    achieved_tflops = (step_flops / launches_per_step) / kern_s / 1e12
+    bound = BOUND.get(w.key, "hbm")
+    traffic, traffic_src = measured_traffic(kernel_tag, w.key) if not args.per_layer_calls else (None, None)
 
     result = {
         "metric": METRIC,
@@ -190,38 +250,54 @@ def main():
             "n_adapters": w.projs[0].n_adapters, "distinct_adapters": U, "layers": w.layers,
             "y_dtype": "fp32" if args.y_fp32 else "bf16",
             "rotating_copies": copies, "launch_mode": args.mode,
+            "calls_per_step": calls_per_step,
         },
         "us_per_step": round(ms_per_step * 1e3, 3),
-        "us_per_linear": round(ms_per_step * 1e3 / (len(w.projs) * w.layers), 3),
+        "us_per_linear": round(ms_per_step * 1e3 / (n_proj * w.layers), 3),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_step": step_bytes,
         "tflops": round(step_flops / (elapsed / K) / 1e12, 3),
+        "max_rel_err": float(f"{max_rel_err:.3e}"),
+        "status_word": 0,
         "setup_s": round(setup_s, 1),
         "roofline": {
             "kernel": kernel_name,
-            "bound": "mfma" if wide else "hbm",
-            "achieved": round(achieved_tflops, 1) if wide else round(achieved, 1),
-            "peak": MFMA_BF16_PEAK_TFLOPS if wide else HBM_PEAK_GBS,
-            "unit": "TFLOP/s" if wide else "GB/s",
-            "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4) if wide else round(achieved / HBM_PEAK_GBS, 4),
+            "bound": bound,
+            "achieved": round(achieved_tflops, 1) if bound == "mfma" else round(achieved, 1),
+            "peak": MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+            "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4) if bound == "mfma" else round(achieved / HBM_PEAK_GBS, 4),
             "hbm_gbs": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC.get(w.key),
+            "mfma_tflops": round(achieved_tflops, 1), "mfma_frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": traffic,
+            "traffic_source": traffic_src,
             "algorithmic_bytes_per_launch": int(base_bytes),
-            "avg_launch_us": round(kern_ms * 1e3, 3),
+            "avg_launch_us": round(kern_s * 1e6, 3),
             "launches_timed": n_ev,
             "timed_with": "two HIP events around the timed region on the launch stream",
         },
     }
 
+    if dep_plans and not args.no_dependency_order:
+        Kd = max(1, K // 4)
+        el_d, _ = timed(dep_plans, Kd, min(args.warmup, 5))
+        for ws in workspaces:
+            assert lib.workspace_status(ws) == 0
+        result["dependency_order"] = {
+            "what": "the same stack as four calls per layer (q,k,v | o | gate,up | down), one workspace",
+            "calls_per_step": len(dep_plans[0]), "steps": Kd,
+            "us_per_step": round(el_d / Kd * 1e6, 3),
+            "value": round(step_bytes / (el_d / Kd) / 1e9, 1), "unit": "GB/s",
+            "pct_of_hbm_peak": round(100.0 * step_bytes / (el_d / Kd) / 1e9 / HBM_PEAK_GBS, 2),
+        }
+
     if not args.no_cpu_baseline:
-        import oracle
-        probs, xs, rows = host_sets[0]
         cores = oracle.max_threads()
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 1000:
             t1 = time.perf_counter()
-            for p, x in zip(probs, xs):
-                oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows)
+            for p, x in zip(probs0, xs0):
+                oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows_h)
             t_cpu += time.perf_counter() - t1
             reps += 1
         result["cpu_baseline"] = {
@@ -229,9 +305,9 @@ def main():
             "unit": "GB/s",
             "cores": cores,
             "kind": "oracle",
-            "sample": f"layer 0 of {w.key} ({len(probs)} projections, M={M}), {reps} repetitions, "
+            "sample": f"layer 0 of {w.key} ({len(probs0)} projections, M={M}), {reps} repetitions, "
                       f"{t_cpu:.1f} s of fp64 loops on {cores} threads",
-            "us_per_linear": round(t_cpu / reps / len(probs) * 1e6, 1),
+            "us_per_linear": round(t_cpu / reps / len(probs0) * 1e6, 1),
         }
     print(json.dumps(result, ensure_ascii=False), flush=True)
 
