@@ -74,7 +74,7 @@ int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 1
 // (fewer partial sums for every finishing block to gather).
 int kch_of(const mlora_w4_proj &p, int M)
 {
-    const int c = p.K / ((M > 16 && M < WIDE_MIN_ROWS) ? 512 : 1024);
+    const int c = p.K / ((M > 16 && M <= 32) ? 512 : 1024);
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 size_t t_part_bytes(const mlora_w4_proj &p, int M)
@@ -84,20 +84,20 @@ size_t t_part_bytes(const mlora_w4_proj &p, int M)
 
 int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
 
-// K units per column tile.  Decode kernels: units of at most 2048 inputs (16 super-steps: what a
-// block stages of x).  Wide kernel (33 rows and more): any unit length works.  A launch whose
-// base blocks with such units (`launch_blocks`) would leave most compute units idle gets shorter
-// units, the same length for all its projections: 8 super-steps up to 240 blocks, 4 below 80.
+// K units per column tile.  Tile blocks: units of at most 2048 inputs (16 super-steps: what a
+// block stages of x).  Wide blocks: any unit length works.  A wide launch whose base blocks with
+// such units (`launch_blocks`) would leave most compute units idle gets shorter units, the same
+// length for all its projections: 8 super-steps up to 240 blocks, 4 below 80.
 // Measured on single projections and on whole layers: up to 64 rows about 200 to 250 base
 // blocks (one per compute unit with the shrink blocks) beat both fewer and more; a layer of 128
 // rows (232 blocks) gains a quarter from 464 shorter ones, two per compute unit; from 256 rows on
 // (464 blocks and more) the long units win, and not splitting long projections at all is far
 // worse at any size (their blocks finish last).
-int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
+int ksplit_of(const mlora_w4_proj &p, bool wide, int launch_blocks)
 {
     const int nss = p.K / SUPER_K;
     int ks = (nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS;
-    if (M >= WIDE_MIN_ROWS && launch_blocks > 0 && launch_blocks <= 240) {
+    if (wide && launch_blocks > 0 && launch_blocks <= 240) {
         const int unit = launch_blocks < 80 ? 4 : 8;
         const int cut = (nss + unit / 2) / unit;
         if (cut > ks) ks = cut;
@@ -105,20 +105,27 @@ int ksplit_of(const mlora_w4_proj &p, int M, int launch_blocks)
     return ks;
 }
 // base blocks of a launch over `count` projections with the default K units
-int launch_blocks_of(const mlora_w4_proj *projs, int count, int M)
+int launch_blocks_of(const mlora_w4_proj *projs, int count, int M, bool wide)
 {
     int n = 0;
     const int chunks = m_pad_of(M) / rows_per_chunk(M);
     for (int i = 0; i < count; ++i) {
         const int nss = projs[i].K / SUPER_K;
-        n += (tiles_n(projs[i].N) + tiles_per_block(M) - 1) / tiles_per_block(M) * chunks *
+        n += (tiles_n(projs[i].N) + tiles_per_block(wide) - 1) / tiles_per_block(wide) * chunks *
              ((nss + UNIT_SUPER_STEPS - 1) / UNIT_SUPER_STEPS);
     }
     return n;
 }
-size_t partial_bytes(const mlora_w4_proj &p, int M, int launch_blocks)
+// Which family of base blocks a launch over these projections runs (see common.hpp).
+bool launch_is_wide(const mlora_w4_proj *projs, int count, int M)
 {
-    return (size_t)(ksplit_of(p, M, launch_blocks) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
+    if (M >= WIDE_ALWAYS_ROWS) return true;
+    if (M < WIDE32_MIN_ROWS) return false;
+    return launch_blocks_of(projs, count, M, true) >= WIDE32_MIN_BLOCKS;
+}
+size_t partial_bytes(const mlora_w4_proj &p, int M, bool wide, int launch_blocks)
+{
+    return (size_t)(ksplit_of(p, wide, launch_blocks) - 1) * (size_t)tiles_n(p.N) * (size_t)m_pad_of(M) * TILE_N * sizeof(float);
 }
 
 }  // namespace
@@ -179,13 +186,14 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
                              (hipStream_t)stream) == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }
 
-// Projections of one launch: up to MAX_PROJ_PER_LAUNCH, and for the wide kernel (33 rows and
-// more, compiled per group size) only as long as the group size stays the same.
+// Projections of one launch: up to MAX_PROJ_PER_LAUNCH, and where wide blocks are possible (17
+// rows and more; those kernels are compiled per group size) only as long as the group size
+// stays the same.
 static int launch_run(const mlora_w4_proj *projs, int n_left, int M)
 {
     int count = 1;
     while (count < n_left && count < MAX_PROJ_PER_LAUNCH &&
-           (M < WIDE_MIN_ROWS || projs[count].group == projs[0].group))
+           (M < WIDE32_MIN_ROWS || projs[count].group == projs[0].group))
         ++count;
     return count;
 }
@@ -205,7 +213,8 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
                                 char *ctrl, char *data)
 {
     const int chunks = m_pad_of(M) / rows_per_chunk(M);
-    const int lb = launch_blocks_of(projs, count, M);
+    const bool wide = launch_is_wide(projs, count, M);
+    const int lb = launch_blocks_of(projs, count, M, wide);
     const int groups = (count + GROUP_PROJ - 1) / GROUP_PROJ;
     bool shared = false;                       // anything handed from block to block?
     size_t part_lines = 0, data_bytes = 0;
@@ -221,7 +230,7 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
         for (int i = z * GROUP_PROJ; i < count && i < (z + 1) * GROUP_PROJ; ++i) {
             const mlora_w4_proj &p = projs[i];
             const int tiles = tiles_n(p.N);
-            const int ksplit = ksplit_of(p, M, lb);
+            const int ksplit = ksplit_of(p, wide, lb);
             // The kernels divide a block index by the tile count with a multiplication that is
             // exact while index * tiles < 2^32: a projection with more than 2^15 column tiles and
             // K units to match is refused rather than mis-indexed.
@@ -229,8 +238,8 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
                 return MLORA_ESHAPE;
             const bool lora = lora_on && p.n_adapters > 0;
             // base blocks: one per column tile, or per four of them in the wide kernel
-            const int col_blocks = (tiles + tiles_per_block(M) - 1) / tiles_per_block(M);
-            const size_t part_bytes = partial_bytes(p, M, lb);
+            const int col_blocks = (tiles + tiles_per_block(wide) - 1) / tiles_per_block(wide);
+            const size_t part_bytes = partial_bytes(p, M, wide, lb);
             const size_t t_bytes = lora ? t_part_bytes(p, M) : 0;
             const int n_shrink = !lora ? 0
                 : (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *
@@ -250,7 +259,7 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
                 d.ksplit = ksplit;
                 // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
                 // finishing ones, or every K unit where the LoRA term is spread over them
-                d.n_finish_blocks = tiles * chunks * (M >= WIDE_MIN_ROWS ? ksplit : 1);
+                d.n_finish_blocks = tiles * chunks * (wide ? ksplit : 1);
                 d.unit_q = (p.K / SUPER_K) / ksplit;
                 d.unit_r = (p.K / SUPER_K) % ksplit;
                 d.spg_shift = d.spg == 4 ? 2 : d.spg == 2 ? 1 : 0;
@@ -300,7 +309,10 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
     need.data_bytes = data_bytes;
     need.grid_x = grid_x;
     need.groups = groups;
-    if (a) a->ctrl = reinterpret_cast<unsigned *>(ctrl);
+    if (a) {
+        a->ctrl = reinterpret_cast<unsigned *>(ctrl);
+        a->wide = wide;
+    }
     return MLORA_OK;
 }
 

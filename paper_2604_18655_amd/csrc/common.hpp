@@ -122,6 +122,7 @@ struct LayerArgs {
     int y_fp32;
     int m_pad;                 // M rounded up to whole row chunks of the base kernel
     int spin_limit;            // polls a block makes before it gives up waiting (0: gives up at once)
+    int wide;                  // the launch runs wide blocks (see below)
     unsigned *ctrl;            // completion counters of this launch
     unsigned *status;          // workspace status word: set non-zero if a wait ran out
     uint32_t code_mask;        // 0x00780078: the two code fields of a bf16 pair
@@ -185,12 +186,18 @@ hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t 
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
-// Calls with at least this many rows take the wide kernel (chunks of 64 rows): from 33 rows on
-// the 32-row kernel would stream the weights twice (measured: 54 -> 44 us for a c2-shaped layer).
-constexpr int WIDE_MIN_ROWS = 33;
+// Two families of base blocks.  "Tile" blocks cover one column tile and their four waves split
+// K (many short-lived blocks: what a small launch needs to fill the chip); "wide" blocks cover
+// four column tiles, one per wave, and share the rows of x through LDS (a quarter of the x
+// traffic and no reduction across waves: what a long weight stream needs).  Up to 16 rows: tile
+// blocks.  33 rows and more: wide blocks with chunks of 64 rows.  17 to 32 rows (chunks of 32
+// rows): wide blocks if the launch has at least WIDE32_MIN_BLOCKS of them, else tile blocks.
+constexpr int WIDE_ALWAYS_ROWS = 33;
+constexpr int WIDE32_MIN_ROWS = 17;
+constexpr int WIDE32_MIN_BLOCKS = 300;
 constexpr int WIDE_TILES_PER_BLOCK = 4;
-__host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : M < WIDE_MIN_ROWS ? 32 : 64; }
+__host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : 64; }
 // column tiles a base block covers
-__host__ __device__ inline int tiles_per_block(int M) { return M < WIDE_MIN_ROWS ? 1 : WIDE_TILES_PER_BLOCK; }
+__host__ __device__ inline int tiles_per_block(bool wide) { return wide ? WIDE_TILES_PER_BLOCK : 1; }
 
 }  // namespace mlora

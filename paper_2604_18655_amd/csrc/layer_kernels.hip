@@ -22,6 +22,8 @@
 // rows of A[adapter]); the partial sums go to t_part[chunk][row][rank].  Up to 16 rows: a block
 // per (row, 16 ranks, K chunk).  More rows: the rows of a chunk of 64 are grouped by adapter
 // and cut into tiles of 16, and a block's waves each take whole tiles.
+#include <type_traits>
+
 #include "group_rows.hpp"
 
 namespace mlora {
@@ -56,6 +58,13 @@ __device__ __forceinline__ f32x4_t load_shared16(const float *p)
     f32x4_t v;
     asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(v) : "v"(p) : "memory");
     return v;
+}
+__device__ __forceinline__ void shared16_wait(f32x4_t (&v)[8])
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
+                 :
+                 : "memory");
 }
 __device__ __forceinline__ void shared16_wait(f32x4_t (&v)[16])
 {
@@ -1190,13 +1199,19 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
 // MFMA pair per 16 columns and 32 ranks adds B[a] . t for every block of 16 rows that holds such
 // a row, the rows of other adapters masked to zero.
 // ------------------------------------------------------------------------------------------
-constexpr int WIDE_ROWS = 64, WIDE_TILES = 4;
+constexpr int WIDE_TILES = 4;
 
+// MB blocks of 16 rows per chunk: 4 (64 rows) from 33 rows on, 2 (32 rows) for 17 to 32 rows.
+// A stage of x holds XSTEPS k-steps of every row of the chunk: one super-step (4 k-steps) at 64
+// rows, two at 32 rows.
+template <int MB>
 struct WideLds {
-    static constexpr int XROW = 4 * 64 + 16;               // bytes of a row of x per super-step; +16: rows 4 banks apart
-    static constexpr int X_STAGE = WIDE_ROWS * XROW;
+    static constexpr int ROWS = 16 * MB;
+    static constexpr int XSTEPS = MB == 2 ? 8 : 4;
+    static constexpr int XROW = XSTEPS * 64 + 16;          // bytes of a row of x per stage; +16: rows 4 banks apart
+    static constexpr int X_STAGE = ROWS * XROW;
     static constexpr int T_STRIDE = MLORA_MAX_RANK + 4;    // floats per row of t
-    static constexpr int T_BYTES = WIDE_ROWS * T_STRIDE * 4;
+    static constexpr int T_BYTES = ROWS * T_STRIDE * 4;
     static constexpr int BUF_BYTES = 2 * X_STAGE > T_BYTES ? 2 * X_STAGE : T_BYTES;
     alignas(16) unsigned char buf[BUF_BYTES];              // x stages; after the K loop: t
     alignas(16) float stage[WIDE_TILES][16 * (TILE_N + 4)]; // per wave: 16 rows of outputs on their way out
@@ -1255,7 +1270,7 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
 #pragma unroll
             for (int t = 0; t < SPG; ++t)
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) xk[t][mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+                for (int mb = 0; mb < 4; ++mb) xk[t][mb] = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
         }
         // offset term of the group: -24 * sum of x over its inputs, per row
         f32x4 corr[4];
@@ -1266,7 +1281,7 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
             for (int t = 0; t < SPG; ++t) {
                 uint4 xa;
                 if constexpr (KEEP_X) xa = xk[t][mb];
-                else xa = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+                else xa = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
                 corr[mb] = mfma16(xa, neg24, corr[mb]);
             }
         }
@@ -1282,7 +1297,7 @@ __device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], 
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
                 if constexpr (KEEP_X) xa[mb] = xk[t][mb];
-                else xa[mb] = xs[mb * WideLds::XROW + (g * SPG + t) * 4];
+                else xa[mb] = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
             }
             const u32x4 wv = r.w[g * SPG + t];
 #pragma unroll
@@ -1311,13 +1326,123 @@ __device__ __forceinline__ void split_bf16(const float (&v)[8], uint4 &hi, uint4
     lo = make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]);
 }
 
-// group = index of the block's four tiles among the projection's; ku as in base_unit.  SPG =
-// k-steps per scale group, the same for every projection of the launch.
+// ------------------------------------------------------------------------------------------
+// 17 to 32 rows: the weight stream is what bounds the call, but the arithmetic per packed
+// byte (unpack, 8 + 2 MFMAs, 32 rescale FMAs per k-step) is close behind, so the K loop is as
+// plain as it can be made.  Per wave: the packed codes and the scales of the next 8 k-steps are
+// in registers (8 KiB in flight), each register set requested again as soon as its k-step is
+// consumed; the rows of x come through LDS in stages of 8 k-steps shared by the block's four
+// waves (one barrier per stage).  The scale multiplies the fp32 sum of a group, as everywhere.
+// ------------------------------------------------------------------------------------------
 template <int SPG>
-__device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P, int pi, int group, int ku,
-                                          int m0, WideLds &lds)
+__device__ __forceinline__ void stream32_loop(f32x4 (&acc)[2][4], const u32x4 *wp, const uint2 *sp,
+                                              const unsigned char *const (&xrow)[4], int piece16, const int (&xdst)[4],
+                                              unsigned char *lds_x, const unsigned char *xfrag, int n_ksteps,
+                                              uint32_t mask, uint32_t bias)
 {
-    using L = WideLds;
+    using L = WideLds<2>;
+    constexpr int S = L::XSTEPS;                           // k-steps per stage (and registers sets per wave)
+    static_assert(S % SPG == 0, "a stage holds whole scale groups");
+    const u32x4 neg24 = {0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u};
+    const int last = n_ksteps - 1;
+    u32x4 w[S];
+    uint2 sc[S / SPG];
+    u32x4 xr[4];
+    // (requests past the unit's end re-read its last k-step: all loads stay unconditional)
+    const int x_last = n_ksteps * 64 - 16;                 // last 16-byte piece of a row inside the unit
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xrow[i] + min(piece16, x_last));
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+        const int kc = min(k, last);
+        w[k] = __builtin_nontemporal_load(wp + kc * 64);
+        if (k % SPG == 0) sc[k / SPG] = sp[(kc / SPG) * 16];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds_x + xdst[i]) = xr[i];
+    const int n_stages = (n_ksteps + S - 1) / S;
+#pragma nounroll
+    for (int st = 0; st < n_stages; ++st) {
+        __syncthreads();                                   // this stage's rows of x are in place; the other buffer is free
+        const int buf = (st & 1) * L::X_STAGE;
+        const int x_off = min(min(st + 1, n_stages - 1) * S * 64 + piece16, x_last);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xrow[i] + x_off);
+        // the math of NK k-steps of this stage (NK = S, or 4 in the last stage of a unit that ends
+        // on an odd super-step): one straight piece of code, no branches inside
+        auto stage_math = [&](auto nk) {
+            constexpr int NK = decltype(nk)::value;
+#pragma unroll
+            for (int g = 0; g < NK / SPG; ++g) {
+                // the fragments of x of a group stay in registers for the offset term and the
+                // products alike when the group is short (up to 2 k-steps); longer groups read them twice
+                constexpr bool KEEP_X = SPG <= 2;
+                u32x4 xk[KEEP_X ? SPG : 1][2];
+                auto x_frag = [&](int k, int mb) {
+                    return *reinterpret_cast<const u32x4 *>(xfrag + buf + mb * 16 * L::XROW + k * 64);
+                };
+                // offset term of the group: -24 * sum of x over its inputs cancels the offset of the stored codes
+                f32x4 corr[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                for (int t = 0; t < SPG; ++t)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        const u32x4 xa = x_frag(g * SPG + t, mb);
+                        if constexpr (KEEP_X) xk[t][mb] = xa;
+                        corr[mb] = mfma16(__builtin_bit_cast(uint4, xa), __builtin_bit_cast(uint4, neg24), corr[mb]);
+                    }
+                f32x4 d[2][4];
+#pragma unroll
+                for (int t = 0; t < SPG; ++t) {
+                    const int k = g * SPG + t;
+                    u32x4 xa[2];
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        if constexpr (KEEP_X) xa[mb] = xk[t][mb];
+                        else xa[mb] = x_frag(k, mb);
+                    }
+                    const u32x4 wv = w[k];
+                    const int kc = min((st + 1) * S + k, last);
+                    w[k] = __builtin_nontemporal_load(wp + kc * 64);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint4 wb = expand_codes(wv[j], mask, bias);
+#pragma unroll
+                        for (int mb = 0; mb < 2; ++mb)
+                            d[mb][j] = mfma16(__builtin_bit_cast(uint4, xa[mb]), wb, t == 0 ? corr[mb] : d[mb][j]);
+                    }
+                }
+                const uint2 sv = sc[g];
+                const int gc = min(((st + 1) * S + g * SPG), last) / SPG;
+                sc[g] = sp[gc * 16];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
+                             : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
+                    asm volatile("" : "+v"(sj));           // a float in a register: plain fp32 FMAs below
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][j][e], sj, acc[mb][j][e]);
+                }
+            }
+        };
+        if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
+        else                        stage_math(std::integral_constant<int, 4>{});
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds_x + (L::X_STAGE - buf) + xdst[i]) = xr[i];
+    }
+}
+
+// group = index of the block's four tiles among the projection's; ku as in base_unit.  SPG =
+// k-steps per scale group, the same for every projection of the launch; MB = blocks of 16 rows
+// per chunk (2: calls of 17 to 32 rows, 4: 33 rows and more).
+template <int SPG, int MB>
+__device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P, int pi, int group, int ku,
+                                          int m0, WideLds<MB> &lds)
+{
+    using L = WideLds<MB>;
+    constexpr int ROWS = L::ROWS;
     const int K = P.K, N = P.N, M = a.M;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lq = lane >> 4;
@@ -1326,7 +1451,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     const bool tile_ok = tile_raw < tiles;                 // (uniform per wave; a spare wave computes and drops tile 0)
     const int tile = tile_ok ? tile_raw : 0;
 
-    const int nss = K / SUPER_K;
     const int uq = P.unit_q, ur = P.unit_r;
     const int unit_beg = ku * uq + min(ku, ur), unit_cnt = uq + (ku < ur ? 1 : 0);
     const int ksteps = K / KSTEP;
@@ -1339,8 +1463,8 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     // blocks alone can fetch in good time.  So every unit waits for the shrink blocks, and
     // P.n_finish_blocks counts (tile, chunk, unit) triples here.
     const bool lora = a.row_adapter != nullptr && P.n_adapters > 0;
-    const int rows_here = min(WIDE_ROWS, M - m0);
-    const int chunk = m0 / WIDE_ROWS, chunks = a.m_pad / WIDE_ROWS;
+    const int rows_here = min(ROWS, M - m0);
+    const int chunk = m0 / ROWS, chunks = a.m_pad / ROWS;
     const int fin = tile * chunks + chunk;
     const int user = fin * P.ksplit + ku;
     const int copies = P.ctr_copies;
@@ -1352,6 +1476,28 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     uint32_t bias = a.code_bias;
     asm volatile("" : "+v"(bias));
 
+    f32x4 acc[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if constexpr (MB == 2) {
+        // rows of x: thread t moves, per stage, the 16-byte pieces t + 256 i (i = 0..3) of the
+        // stage's 32 rows x 512 bytes
+        const unsigned char *xrow[4];
+        int xdst[4];
+        const int piece16 = (tid & 31) * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = (tid >> 5) + 8 * i;
+            xrow[i] = reinterpret_cast<const unsigned char *>(P.x + (size_t)(m0 + min(row, rows_here - 1)) * K +
+                                                              (size_t)unit_beg * SUPER_K);
+            xdst[i] = row * L::XROW + piece16;
+        }
+        const unsigned char *xfrag = lds.buf + l16 * L::XROW + lq * 16;
+        stream32_loop<SPG>(acc, wp + lane, sp + l16, xrow, piece16, xdst, lds.buf, xfrag, unit_cnt * 4, mask, bias);
+    } else {
     // rows of x: thread t moves, per stage, 16 bytes of rows t/16 + 16*i (i = 0..3)
     const uint16_t *xsrc[4];
     int xdst[4];
@@ -1363,11 +1509,6 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     }
     const uint4 *xfrag = reinterpret_cast<const uint4 *>(lds.buf) + l16 * (L::XROW / 16) + lq;
 
-    f32x4 acc[4][4];
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     float prev[4] = {1.f, 1.f, 1.f, 1.f};                  // unit of acc per column block (acc = 0: any unit will do)
 
     WideRegs ra, rb;
@@ -1411,6 +1552,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[mb][j][e] *= prev[j];
+    }
 
     // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
     // tile's 64 columns are fetched once and used by every block of 16 rows that holds
@@ -1515,7 +1657,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         // four neighbouring ranks (16 bytes) at a time; requests go out in batches of 4 such
         // quads x 4 chunks so that the round trips overlap.
         const int qpr = r32 / 4;                           // quads per row of t
-        for (int i0 = 0; i0 < WIDE_ROWS * qpr; i0 += 4 * 256) {
+        for (int i0 = 0; i0 < ROWS * qpr; i0 += 4 * 256) {
             f32x4_t v[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -1545,7 +1687,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                 const int idx = i0 + q * 256 + tid;
                 const int ml = idx / qpr, jj = (idx % qpr) * 4;
                 const bool live = ml < rows_here && jj < P.r16;
-                if (ml < WIDE_ROWS)
+                if (ml < ROWS)
                     *reinterpret_cast<f32x4_t *>(tl + ml * L::T_STRIDE + jj) = live ? v[q] * P.alpha : f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
@@ -1558,7 +1700,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                     const int kk = r.kk0 + (r.nk == 2 ? (b & 1) : 0);
                     const bool k_ok = 32 * kk + 8 * lq < P.rank;
 #pragma unroll
-                    for (int mb = 0; mb < 4; ++mb) {
+                    for (int mb = 0; mb < MB; ++mb) {
                         if (!((r.sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
                         const bool mine = (r.sames[b] >> (16 * mb + l16)) & 1ull;
                         float tv[8];
@@ -1593,13 +1735,13 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         }
     }
     if (ku > 0) {
-        // A partial tile (64 rows x 64 columns) lies in the workspace in the order of the MFMA
-        // results, block (mb, j) of lane l at ((mb * 4 + j) * 64 + l) * 4: producer and consumer
+        // A partial tile (the chunk's rows x 64 columns) lies in the workspace in the order of the
+        // MFMA results, block (mb, j) of lane l at ((mb * 4 + j) * 64 + l) * 4: producer and consumer
         // use the same mapping, and a lane moves 16 bytes per instruction.
         if (tile_ok) {
             float *dst = P.partial + (((size_t)(ku - 1) * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) store_shared16(dst + (mb * 4 + j) * 256, acc[mb][j]);
             compiler_fence();
@@ -1613,19 +1755,19 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         }
         for (int u = 0; u + 1 < P.ksplit; ++u) {
             const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
-            f32x4_t pv[16];
+            f32x4_t pv[4 * MB];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) pv[i] = load_shared16(src + i * 256);
+            for (int i = 0; i < 4 * MB; ++i) pv[i] = load_shared16(src + i * 256);
             shared16_wait(pv);
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[mb][j] += pv[mb * 4 + j];
         }
     }
     if (poisoned) {
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{1.f, 1.f, 1.f, 1.f} * __uint_as_float(0x7FC00000u);
     }
@@ -1636,7 +1778,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             // neighbouring columns at once instead of 64 single values
             float *st = lds.stage[wave];
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
+            for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -1670,7 +1812,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             }
         } else {
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int m = m0 + 16 * mb + 4 * lq + e;
@@ -1699,15 +1841,16 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
     }
 }
 
+template <int MB>
 constexpr int wide_lds_bytes()
 {
-    return sizeof(WideLds) > sizeof(ShrinkLds) ? (int)sizeof(WideLds) : (int)sizeof(ShrinkLds);
+    return sizeof(WideLds<MB>) > sizeof(ShrinkLds) ? (int)sizeof(WideLds<MB>) : (int)sizeof(ShrinkLds);
 }
 
-template <int SPG>
+template <int SPG, int MB>
 __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
 {
-    __shared__ __align__(16) unsigned char smem[wide_lds_bytes()];
+    __shared__ __align__(16) unsigned char smem[wide_lds_bytes<MB>()];
     const int z = (int)blockIdx.z;
     const LaunchTables tables = pin_launch_args(a, z);
     const int b = (int)blockIdx.x;
@@ -1719,20 +1862,20 @@ __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
         shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
-    WideLds &lds = *reinterpret_cast<WideLds *>(smem);
-    const int m0 = (int)blockIdx.y * WIDE_ROWS;
+    WideLds<MB> &lds = *reinterpret_cast<WideLds<MB> *>(smem);
+    const int m0 = (int)blockIdx.y * 16 * MB;
     if (b < tables.shrink_blocks + tables.pre_base_blocks) {
         const int pb = b - tables.shrink_blocks;
         const int pi = z * GROUP_PROJ + find_proj(tables.pre, pb, first);
         const ProjArgs P = fetch_proj(a, pi);
         const int local = pb - first;
         const int groups = (tiles_n(P.N) + WIDE_TILES - 1) / WIDE_TILES;
-        wide_unit<SPG>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
+        wide_unit<SPG, MB>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
     } else {
         const int mb_ = b - tables.shrink_blocks - tables.pre_base_blocks;
         const int pi = z * GROUP_PROJ + find_proj(tables.main, mb_, first);
         const ProjArgs P = fetch_proj(a, pi);
-        wide_unit<SPG>(a, P, pi, mb_ - first, 0, m0, lds);
+        wide_unit<SPG, MB>(a, P, pi, mb_ - first, 0, m0, lds);
     }
 }
 
@@ -1747,11 +1890,17 @@ static hipError_t launch_instance(const LayerArgs &a, const dim3 &grid, hipStrea
 hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s)
 {
     const dim3 grid((unsigned)grid_x, (unsigned)(a.m_pad / rows_per_chunk(a.M)), (unsigned)groups);
-    if (a.M >= WIDE_MIN_ROWS) {
-        // (the host puts only projections with the same group size into one wide launch)
-        if (a.p[0].spg == 1)      wide_kernel<1><<<grid, dim3(256), 0, s>>>(a);
-        else if (a.p[0].spg == 2) wide_kernel<2><<<grid, dim3(256), 0, s>>>(a);
-        else                      wide_kernel<4><<<grid, dim3(256), 0, s>>>(a);
+    if (a.wide) {
+        // (the host puts only projections with the same group size into one such launch)
+        if (a.M <= 32) {
+            if (a.p[0].spg == 1)      wide_kernel<1, 2><<<grid, dim3(256), 0, s>>>(a);
+            else if (a.p[0].spg == 2) wide_kernel<2, 2><<<grid, dim3(256), 0, s>>>(a);
+            else                      wide_kernel<4, 2><<<grid, dim3(256), 0, s>>>(a);
+        } else {
+            if (a.p[0].spg == 1)      wide_kernel<1, 4><<<grid, dim3(256), 0, s>>>(a);
+            else if (a.p[0].spg == 2) wide_kernel<2, 4><<<grid, dim3(256), 0, s>>>(a);
+            else                      wide_kernel<4, 4><<<grid, dim3(256), 0, s>>>(a);
+        }
         return hipGetLastError();
     }
     if (a.M <= 8)  return launch_instance<1, 8>(a, grid, s);

@@ -136,6 +136,22 @@ def test_wide_shapes(gpu, K, N, G, r, n_ad, M):
     assert np.array_equal(y, y_base)
 
 
+@pytest.mark.parametrize("K,N,G,r,n_ad,M", [
+    (256, 76810, 64, 24, 5, 23),      # 301 blocks of four tiles, ragged last tile, one stage of 8 k-steps
+    (4352, 25605, 32, 16, 9, 19),     # 34 super-steps in 3 K units (11/12: odd, a half stage at the end), split-K sums
+    (640, 77000, 128, 128, 3, 32),    # full chunk, maximum rank, group of 4 k-steps, 5 super-steps
+    (1152, 77777, 32, 8, 40, 17),     # one row into the second block of 16, more adapters than rows
+])
+def test_wide_blocks_at_17_to_32_rows(gpu, K, N, G, r, n_ad, M):
+    """Calls of 17 to 32 rows with 300 and more blocks of four column tiles run the kernel that
+    shares the rows of x through LDS (chunks of 32 rows); smaller launches run one-tile blocks."""
+    prob = random_problem(K + N + M, K, N, G, r, n_ad)
+    rng = np.random.default_rng(M)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    rows = rng.integers(-1, n_ad, size=M).astype(np.int32)
+    check_linear(gpu, prob, x, rows, f"wide32 K{K} N{N} G{G} r{r} a{n_ad} M{M}")
+
+
 def test_wide_extreme_and_zero_scales(gpu):
     """The wide kernel keeps its accumulators in units of the current group's scale: scales that
     jump by many orders of magnitude between groups, and zero scales, must not disturb it."""
