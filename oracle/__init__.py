@@ -14,16 +14,16 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "oracle.c")
+_SRCS = [os.path.join(_HERE, "oracle.c"), os.path.join(_HERE, "tree_attention.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile oracle.c -> liboracle.so (plain gcc, OpenMP over output columns)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile oracle.c and tree_attention.c -> liboracle.so (plain gcc, OpenMP over output columns)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -52,6 +52,10 @@ def _load():
         lib.orc_max_threads.restype = i32
         lib.orc_linear.argtypes = [i32, i32, i32, u8p, u16p, i32, i32, u16p, u16p, C.c_double,
                                    u16p, i32p, i32, f64p, f64p]
+        lib.orc_tree_attention.restype = i32
+        lib.orc_tree_attention.argtypes = [i32, i32, i32, i32, i32, C.c_double,
+                                           u16p, u16p, i32, u16p, u16p, i32, u16p, u16p, i32, i32p,
+                                           u16p, u16p, i32p, u8p, u16p, f64p, f64p]
         for f in (lib.orc_unpack_codes, lib.orc_pack_codes, lib.orc_dequant, lib.orc_quantise,
                   lib.orc_set_threads, lib.orc_linear):
             f.restype = None
@@ -163,3 +167,46 @@ def linear(wq, scales, group, lora_a, lora_b, alpha, x, row_adapter, return_t: b
                        _p(x, C.c_uint16), None if ra is None else _p(ra, C.c_int32), M,
                        _p(y, C.c_double), _p(t, C.c_double))
     return (y, t) if return_t else y
+
+
+def tree_attention(q, k_prefill, v_prefill, k_fprefix, v_fprefix, k_stream, v_stream, len_stream,
+                   k_new, v_new, parent, is_forecast, n_streams: int, scale: float,
+                   return_weights: bool = False):
+    """Masked tree attention over a segmented KV cache (tree_attention.c).  bf16 tensors as uint16:
+    q [M][Hq][D]; k_prefill, v_prefill [Hkv][Lp][D]; k_fprefix, v_fprefix [Hkv][Lf][D];
+    k_stream, v_stream [S][Hkv][cap][D]; len_stream int32 [S]; k_new, v_new [M][Hkv][D];
+    parent int32 [M] (index within the stream, -1 = root); is_forecast uint8 [M].
+    Returns out float64 [M][Hq][D] (and the weights [M][Hq][Lp + Lf + cap + R] if asked)."""
+    q = _arr(q, np.uint16)
+    M, Hq, D = q.shape
+    S = int(n_streams)
+    assert M % S == 0
+    R = M // S
+    k_prefill, v_prefill = _arr(k_prefill, np.uint16), _arr(v_prefill, np.uint16)
+    k_fprefix, v_fprefix = _arr(k_fprefix, np.uint16), _arr(v_fprefix, np.uint16)
+    k_stream, v_stream = _arr(k_stream, np.uint16), _arr(v_stream, np.uint16)
+    k_new, v_new = _arr(k_new, np.uint16), _arr(v_new, np.uint16)
+    Hkv, Lp = k_prefill.shape[0], k_prefill.shape[1]
+    Lf, cap = k_fprefix.shape[1], k_stream.shape[2]
+    assert Hq % Hkv == 0
+    assert k_prefill.shape == v_prefill.shape == (Hkv, Lp, D)
+    assert k_fprefix.shape == v_fprefix.shape == (Hkv, Lf, D)
+    assert k_stream.shape == v_stream.shape == (S, Hkv, cap, D)
+    assert k_new.shape == v_new.shape == (M, Hkv, D)
+    len_stream = _arr(len_stream, np.int32)
+    parent, is_forecast = _arr(parent, np.int32), _arr(is_forecast, np.uint8)
+    assert len_stream.shape == (S,) and parent.shape == (M,) and is_forecast.shape == (M,)
+    assert len_stream.min(initial=0) >= 0 and len_stream.max(initial=0) <= cap
+    out = np.empty((M, Hq, D), np.float64)
+    weights = np.zeros((M, Hq, Lp + Lf + cap + R), np.float64) if return_weights else None
+    u16 = C.c_uint16
+    rc = _load().orc_tree_attention(Hq, Hkv, D, S, R, float(scale),
+                                    _p(k_prefill, u16), _p(v_prefill, u16), Lp,
+                                    _p(k_fprefix, u16), _p(v_fprefix, u16), Lf,
+                                    _p(k_stream, u16), _p(v_stream, u16), cap, _p(len_stream, C.c_int32),
+                                    _p(k_new, u16), _p(v_new, u16), _p(parent, C.c_int32),
+                                    _p(is_forecast, C.c_uint8), _p(q, u16), _p(out, C.c_double),
+                                    None if weights is None else _p(weights, C.c_double))
+    if rc != 0:
+        raise ValueError("parent[] must point to an earlier row of the same stream, or be -1")
+    return (out, weights) if return_weights else out
