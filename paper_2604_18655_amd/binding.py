@@ -17,6 +17,7 @@ exported_symbols = (
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
     "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
     "mlora_w4_layer_step_static",
+    "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
 )
 
 
@@ -30,6 +31,17 @@ class _ProjStruct(C.Structure):
     _fields_ = [("K", C.c_int32), ("N", C.c_int32), ("group", C.c_int32),
                 ("w_blob", C.c_void_p), ("n_adapters", C.c_int32), ("rank", C.c_int32),
                 ("lora_a", C.c_void_p), ("lora_b", C.c_void_p), ("alpha", C.c_float)]
+
+
+class _TreeAttnStruct(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("n_streams", C.c_int32), ("rows_per_stream", C.c_int32), ("scale", C.c_float),
+                ("k_prefill", C.c_void_p), ("v_prefill", C.c_void_p), ("len_prefill", C.c_int32),
+                ("k_fprefix", C.c_void_p), ("v_fprefix", C.c_void_p), ("len_fprefix", C.c_int32),
+                ("k_stream", C.c_void_p), ("v_stream", C.c_void_p), ("cap_stream", C.c_int32),
+                ("len_stream", C.c_void_p),
+                ("k_new", C.c_void_p), ("v_new", C.c_void_p),
+                ("parent", C.c_void_p), ("is_forecast", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -67,6 +79,11 @@ def load_library():
         lib.mlora_w4_layer_step_static.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(vp), vp, i32, i32, vp]
         lib.mlora_w4_workspace_init.restype = C.c_int
         lib.mlora_w4_workspace_init.argtypes = [vp, sz, vp]
+        tp = C.POINTER(_TreeAttnStruct)
+        lib.mlora_tree_attention_workspace_bytes.restype = sz
+        lib.mlora_tree_attention_workspace_bytes.argtypes = [tp]
+        lib.mlora_tree_attention.restype = C.c_int
+        lib.mlora_tree_attention.argtypes = [tp, vp, vp, i32, vp, sz, vp]
         lib.mlora_w4_workspace_status.restype = C.c_int
         lib.mlora_w4_workspace_status.argtypes = [vp, C.POINTER(i32), vp]
         lib.mlora_w4_debug_spin_limit.restype = i32
@@ -213,3 +230,29 @@ def layer_step_static(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_ada
 def layer_step(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,
                y_dtype: int = Y_BF16, workspace=None) -> None:
     LayerPlan(projs, xs, ys, row_adapter, M, y_dtype, workspace).run()
+
+
+class TreeAttention:
+    """Descriptor of a masked tree attention call (include/mlora_tree_attention.h); keeps the
+    tensors it points to alive.  Tensors are torch device tensors in the layouts of the header."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, n_streams: int, rows_per_stream: int,
+                 scale: float, k_prefill, v_prefill, k_fprefix, v_fprefix, k_stream, v_stream, len_stream,
+                 k_new, v_new, parent, is_forecast, len_prefill: int, len_fprefix: int, cap_stream: int):
+        self.keep = (k_prefill, v_prefill, k_fprefix, v_fprefix, k_stream, v_stream, len_stream, k_new, v_new,
+                     parent, is_forecast)
+        self.shape = (n_streams * rows_per_stream, n_q_heads, head_dim)
+        self.struct = _TreeAttnStruct(n_q_heads, n_kv_heads, head_dim, n_streams, rows_per_stream, scale,
+                                      _ptr(k_prefill), _ptr(v_prefill), len_prefill,
+                                      _ptr(k_fprefix), _ptr(v_fprefix), len_fprefix,
+                                      _ptr(k_stream), _ptr(v_stream), cap_stream, _ptr(len_stream),
+                                      _ptr(k_new), _ptr(v_new), _ptr(parent), _ptr(is_forecast))
+
+    def workspace_bytes(self) -> int:
+        return int(load_library().mlora_tree_attention_workspace_bytes(C.byref(self.struct)))
+
+    def run(self, q, out, out_dtype: int, workspace, stream: Optional[int] = None) -> None:
+        n = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(load_library().mlora_tree_attention(C.byref(self.struct), _ptr(q), _ptr(out), out_dtype,
+                                                   _ptr(workspace), n, _stream() if stream is None else stream),
+               "mlora_tree_attention")

@@ -15,9 +15,12 @@ OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE = 0, -1, -2, -3, -4
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "mlora_w4.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(mlora_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("mlora_w4.h", "mlora_tree_attention.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(mlora_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
@@ -180,3 +183,42 @@ def test_binding_raises_with_the_library_message():
     with pytest.raises(lib.MloraError) as e:
         binding._check(ESHAPE, "mlora_w4_linear")
     assert "unsupported shape" in str(e.value)
+
+
+def tree_attn(**kw):
+    f = dict(n_q_heads=8, n_kv_heads=2, head_dim=64, n_streams=2, rows_per_stream=4, scale=0.125,
+             k_prefill=0x1000, v_prefill=0x2000, len_prefill=16, k_fprefix=0x3000, v_fprefix=0x4000, len_fprefix=4,
+             k_stream=0x5000, v_stream=0x6000, cap_stream=32, len_stream=0x7000, k_new=0x8000, v_new=0x9000,
+             parent=0xA000, is_forecast=0xB000)
+    f.update(kw)
+    return binding._TreeAttnStruct(**f)
+
+
+def test_tree_attention_sizes_and_argument_checks():
+    cdll = lib.load_library()
+    t = tree_attn()
+    # blocks of 64 keys, one chunk per block for short segments: 1 prefill + 1 prefix block for all
+    # 8 rows x 4 heads per kv head, (1 + 1) blocks per stream for its 4 rows x 4 heads; 66 floats each
+    want = ((1 + 1) * 2 * 32 + 2 * (1 + 1) * 2 * 16) * 66 * 4 + 256
+    assert cdll.mlora_tree_attention_workspace_bytes(C.byref(t)) == want
+
+    def call(t, q=0xC000, out=0xD000, dt=0, ws=0xE000, ws_bytes=1 << 30):
+        return cdll.mlora_tree_attention(C.byref(t), q, out, dt, ws, ws_bytes, None)
+
+    for bad in (dict(head_dim=96), dict(n_q_heads=7), dict(n_kv_heads=0), dict(rows_per_stream=65),
+                dict(rows_per_stream=0), dict(n_streams=0), dict(n_streams=2000), dict(len_prefill=-1),
+                dict(n_q_heads=64, n_kv_heads=2)):
+        assert cdll.mlora_tree_attention_workspace_bytes(C.byref(tree_attn(**bad))) == 0
+        assert call(tree_attn(**bad)) == ESHAPE
+    for bad in (dict(k_new=None), dict(parent=None), dict(k_prefill=None), dict(v_fprefix=None), dict(len_stream=None)):
+        assert call(tree_attn(**bad)) == EINVAL
+    assert call(tree_attn(k_prefill=None, v_prefill=None, len_prefill=0), ws_bytes=16) == EWORKSPACE   # an empty segment needs no pointer
+    assert call(tree_attn(k_stream=0x5008)) == EALIGN
+    assert call(tree_attn(parent=0xA002)) == EALIGN
+    assert call(t, q=None) == EINVAL
+    assert call(t, dt=3) == EINVAL
+    assert call(t, out=0xD004) == EALIGN
+    assert call(t, ws=None) == EWORKSPACE
+    assert call(t, ws_bytes=want - 1) == EWORKSPACE
+    assert call(t, ws=0xE010) == EALIGN
+    assert cdll.mlora_tree_attention(None, 1, 1, 0, 1, 1, None) == EINVAL
