@@ -45,7 +45,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4_decode",
-                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down")
+                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down, c4_attention")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
                          "eager: one library call per step from Python")
@@ -73,12 +73,127 @@ def measured_traffic(kernel_tag: str, workload: str):
     return (int(m.group(1)), os.path.relpath(path, ROOT)) if m else (None, None)
 
 
+def bench_attention(args):
+    """--workload c4_attention: the masked tree attention of the 16-layer stack's decoding step
+    (8 streams x 4 tree rows, 32 query heads on 8 kv heads of 64 features, 2048 prefill
+    positions, up to 128 positions per stream), one call per layer, 16 calls per step."""
+    import numpy as np
+    import torch
+
+    import oracle
+    import paper_2604_18655_amd as lib
+    import workloads as wl
+    from paper_2604_18655_amd import device
+
+    lib.load_library()
+    torch.cuda.set_device(0)
+    S, Hq, Hkv, D, Lp, Lf, cap, layers = 8, 32, 8, 64, 2048, 0, 128, 16
+    parent, fc = np.asarray([-1, 0, 0, 1], np.int32), np.zeros(4, np.uint8)
+    R, M = 4, 32
+    copies = args.copies or 9                         # 9 x 16 layers x 6 MB > 3 x 256 MiB
+    dev = lambda a: device.to_device(a) if a.size else None
+    calls, host0 = [], None
+    t0 = time.time()
+    step_bytes = 0
+    for c in range(copies):
+        for layer in range(layers):
+            inp = wl.make_attention_inputs(1000 + c * layers + layer, S, parent, fc, Hq, Hkv, D, Lp, Lf, cap)
+            t = lib.TreeAttention(Hq, Hkv, D, S, R, inp.scale, dev(inp.k_prefill), dev(inp.v_prefill),
+                                  dev(inp.k_fprefix), dev(inp.v_fprefix), dev(inp.k_stream), dev(inp.v_stream),
+                                  torch.from_numpy(inp.len_stream).cuda(), dev(inp.k_new), dev(inp.v_new),
+                                  torch.from_numpy(inp.parent).cuda(), torch.from_numpy(inp.is_forecast).cuda(),
+                                  Lp, Lf, cap)
+            q = device.to_device(inp.q)
+            out = torch.empty((M, Hq, D), dtype=torch.int16, device="cuda")
+            ws = torch.empty(max(t.workspace_bytes(), 256), dtype=torch.uint8, device="cuda")
+            calls.append((t, q, out, ws))
+            if c == 0:
+                # what a call has to move at least once: visible keys and values, q, the rows' k and v, out
+                step_bytes += 2 * 2 * Hkv * D * (Lp + Lf + int(inp.len_stream.sum())) + 2 * 2 * M * Hkv * D + 2 * 2 * M * Hq * D
+            if c == 0 and layer == 0:
+                host0 = inp
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def run_step(i, stream=None):
+        base = (i % copies) * layers
+        for t, q, out, ws in calls[base:base + layers]:
+            t.run(q, out, lib.Y_BF16, ws, stream)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(K):
+                run_step(args.warmup + i, side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev0.record()
+    graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    call_s = ev0.elapsed_time(ev1) * 1e-3 / (K * layers)
+
+    ref = oracle.tree_attention(host0.q, host0.k_prefill, host0.v_prefill, host0.k_fprefix, host0.v_fprefix,
+                                host0.k_stream, host0.v_stream, host0.len_stream, host0.k_new, host0.v_new,
+                                host0.parent, host0.is_forecast, S, host0.scale)
+    got = device.y_to_numpy(calls[0][2].reshape(M, Hq * D)).reshape(M, Hq, D)
+    max_rel_err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    assert max_rel_err <= 5e-3, max_rel_err
+    gbs = step_bytes / (elapsed / K) / 1e9
+    call_bytes = step_bytes / layers
+    result = {
+        "metric": "µs per masked tree attention call + achieved HBM GB/s (% of 8 TB/s), 1 MI355X",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / K, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_attention: tree attention of the 16-layer stack's decoding step, one call per layer",
+                   "streams": S, "rows_per_stream": R, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D,
+                   "len_prefill": Lp, "len_fprefix": Lf, "cap_stream": cap, "layers": layers,
+                   "rotating_copies": copies, "launch_mode": "graph"},
+        "us_per_step": round(elapsed * 1e6 / K, 3), "us_per_call": round(elapsed * 1e6 / K / layers, 3),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2), "algorithmic_bytes_per_step": step_bytes,
+        "max_rel_err": float(f"{max_rel_err:.3e}"), "setup_s": round(setup_s, 1),
+        "roofline": {"kernel": "tree_attn_partial<64> + tree_attn_combine<64> (one call)", "bound": "hbm",
+                     "achieved": round(call_bytes / call_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(call_bytes / call_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(call_bytes), "avg_launch_us": round(call_s * 1e6, 3),
+                     "launches_timed": K * layers,
+                     "timed_with": "two HIP events around the timed region on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 100:
+            t1 = time.perf_counter()
+            oracle.tree_attention(host0.q, host0.k_prefill, host0.v_prefill, host0.k_fprefix, host0.v_fprefix,
+                                  host0.k_stream, host0.v_stream, host0.len_stream, host0.k_new, host0.v_new,
+                                  host0.parent, host0.is_forecast, S, host0.scale)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        result["cpu_baseline"] = {"value": round(call_bytes * reps / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                  "kind": "oracle", "sample": f"layer 0, {reps} repetitions, {t_cpu:.1f} s of fp64 loops on 1 thread",
+                                  "us_per_call": round(t_cpu / reps * 1e6, 1)}
+    print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards along N, see DESIGN.md); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "c4_attention":
+        bench_attention(args)
+        return
 
     import numpy as np
     import torch

@@ -42,7 +42,7 @@ extern "C" {
 #endif
 
 typedef struct {
-    int32_t n_q_heads, n_kv_heads;   /* n_q_heads % n_kv_heads == 0, at most 16 query heads per kv head */
+    int32_t n_q_heads, n_kv_heads;   /* n_q_heads % n_kv_heads == 0, at most 8 query heads per kv head */
     int32_t head_dim;                /* 64 or 128 */
     int32_t n_streams;               /* S */
     int32_t rows_per_stream;         /* R, 1..64; S * R <= MLORA_MAX_ROWS */

@@ -21,8 +21,10 @@ namespace mlora {
 namespace {
 
 constexpr int KC = 64;                   // keys per chunk
-// query tiles (of 16 vectors) a wave carries at most, and query vectors per block (more: grid.z slices)
-constexpr int qt_per_wave(int D) { return D <= 64 ? 4 : 2; }
+// Query tiles (of 16 vectors) a wave carries, and query vectors per block (more: grid.z slices).
+// One tile per wave: a block runs its code once, so what counts is how little code there is (a
+// second tile per wave would be a second copy of the whole tile body, fetched cold).
+constexpr int qt_per_wave(int) { return 1; }
 constexpr int qv_per_slice(int D) { return 16 * 4 * qt_per_wave(D); }
 constexpr float NEG_BIG = -1.0e30f;      // "no key seen yet"
 
@@ -57,20 +59,27 @@ struct AttnLds {
     unsigned long long anc[64];                          // rows of the step a row may see (bit j = row j)
 };
 
+// Reductions over the 16 lanes that hold the keys of one row of scores: four rotations within
+// the row of 16 lanes (DPP row_ror 8, 4, 2, 1), after which every lane holds the result.
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
+}
 __device__ __forceinline__ float wave16_max(float v)
 {
-    v = fmaxf(v, __shfl_xor(v, 1));
-    v = fmaxf(v, __shfl_xor(v, 2));
-    v = fmaxf(v, __shfl_xor(v, 4));
-    v = fmaxf(v, __shfl_xor(v, 8));
+    v = fmaxf(v, row_ror<8>(v));
+    v = fmaxf(v, row_ror<4>(v));
+    v = fmaxf(v, row_ror<2>(v));
+    v = fmaxf(v, row_ror<1>(v));
     return v;
 }
 __device__ __forceinline__ float wave16_sum(float v)
 {
-    v += __shfl_xor(v, 1);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 8);
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    v += row_ror<1>(v);
     return v;
 }
 
@@ -268,13 +277,13 @@ __global__ __launch_bounds__(256) void tree_attn_partial(const AttnArgs a)
     }
 }
 
-// One block of D threads per (row, query head): merge what the blocks of the first kernel saw, in
-// the order prefill, forecast prefix, own stream segment, rows of the step.
+// One block per (row, kv head), D threads per query head of the group: merge what the blocks of
+// the first kernel saw, in the order prefill, forecast prefix, own stream segment, rows of the step.
 template <int D>
-__global__ __launch_bounds__(D) void tree_attn_combine(const AttnArgs a)
+__global__ __launch_bounds__(1024) void tree_attn_combine(const AttnArgs a)
 {
-    const int m = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
-    const int hk = hq / a.G, g = hq % a.G, s = m / a.R, i = m % a.R;
+    const int m = blockIdx.x, hk = blockIdx.y, d = threadIdx.x % D, g = threadIdx.x / D;
+    const int hq = hk * a.G + g, s = m / a.R, i = m % a.R;
     const int n_all = a.M * a.G, n_str = a.R * a.G;
     const bool fc = a.is_forecast[m] != 0;
     const int stream_blocks = a.cap > 0 ? min(a.nb_stream, (max(0, min(a.len_stream[s], a.cap)) + KC * a.cpb - 1) / (KC * a.cpb)) : 0;
@@ -286,18 +295,33 @@ __global__ __launch_bounds__(D) void tree_attn_combine(const AttnArgs a)
         const int blk = j < stream_blocks ? j : a.nb_stream;          // (the rows of the step sit in the last slot)
         return a.part_stream + ((((size_t)s * (a.nb_stream + 1) + blk) * a.Hkv + hk) * n_str + (size_t)i * a.G + g) * (D + 2);
     };
-    float top = NEG_BIG;
-    for (int j = 0; j < n_src; ++j) {
-        const float *p = src(j);
-        if (p[1] > 0.f) top = fmaxf(top, p[0]);
-    }
-    float num = 0.f, den = 0.f;
-    for (int j = 0; j < n_src; ++j) {
-        const float *p = src(j);
-        if (!(p[1] > 0.f)) continue;
-        const float w = __expf(p[0] - top);
-        den += w * p[1];
-        num += w * p[2 + d];
+    // Sources in rounds of 8: every thread requests the round's maxima, sums and its own feature
+    // of the outputs all at once (one memory round trip per round; the maxima and sums are the
+    // same addresses for all threads of the block), then folds the round into the running result.
+    constexpr int RB = 8;
+    float num = 0.f, den = 0.f, run_top = NEG_BIG;
+    for (int j0 = 0; j0 < n_src; j0 += RB) {
+        float pm[RB], pl[RB], pv[RB];
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const float *p = src(min(j0 + u, n_src - 1));
+            pm[u] = p[0];
+            pl[u] = j0 + u < n_src ? p[1] : 0.f;
+            pv[u] = p[2 + d];
+        }
+        float top = run_top;
+#pragma unroll
+        for (int u = 0; u < RB; ++u) top = pl[u] > 0.f ? fmaxf(top, pm[u]) : top;
+        const float keep = __expf(run_top - top);          // (1 while nothing has been seen)
+        num *= keep;
+        den *= keep;
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const float w = pl[u] > 0.f ? __expf(pm[u] - top) : 0.f;
+            num += w * pv[u];
+            den += w * pl[u];
+        }
+        run_top = top;
     }
     const float r = num / den;                             // (a row always sees itself: den > 0)
     const size_t at = ((size_t)m * a.Hq + hq) * D + d;
@@ -307,12 +331,15 @@ __global__ __launch_bounds__(D) void tree_attn_combine(const AttnArgs a)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// chunks a block walks through: long segments get longer runs, so that what the blocks leave in
-// the workspace stays well below what they read
-int chunks_per_block(int longest)
+// Chunks a block walks through.  One, as long as that gives at most about a thousand blocks per
+// segment (blocks are short, and what bounds a call of this size is the latency of a block, not
+// the bytes it moves); longer runs for longer segments, so that what the blocks leave in the
+// workspace stays well below what they read.
+int chunks_per_block(int longest, int n_kv_heads)
 {
-    const int chunks = (longest + KC - 1) / KC;
-    return chunks <= 8 ? 1 : chunks <= 32 ? 2 : 4;
+    const long long chunks = (longest + KC - 1) / KC;
+    const long long cpb = (chunks * n_kv_heads + 1023) / 1024;
+    return cpb < 1 ? 1 : cpb > 16 ? 16 : (int)cpb;
 }
 
 struct Plan {
@@ -326,7 +353,7 @@ Plan plan_of(const mlora_tree_attn &t)
     const int G = t.n_q_heads / t.n_kv_heads;
     const int M = t.n_streams * t.rows_per_stream;
     const int longest = t.len_prefill > t.cap_stream ? t.len_prefill : t.cap_stream;
-    p.cpb = chunks_per_block(longest > t.len_fprefix ? longest : t.len_fprefix);
+    p.cpb = chunks_per_block(longest > t.len_fprefix ? longest : t.len_fprefix, t.n_kv_heads);
     auto blocks = [&](int len) { return ((len + KC - 1) / KC + p.cpb - 1) / p.cpb; };
     p.nb_prefill = blocks(t.len_prefill);
     p.nb_fprefix = blocks(t.len_fprefix);
@@ -342,7 +369,7 @@ mlora_status check(const mlora_tree_attn *t)
     if (!t) return MLORA_EINVAL;
     if (t->head_dim != 64 && t->head_dim != 128) return MLORA_ESHAPE;
     if (t->n_kv_heads <= 0 || t->n_q_heads <= 0 || t->n_q_heads % t->n_kv_heads != 0) return MLORA_ESHAPE;
-    if (t->n_q_heads / t->n_kv_heads > 16 || t->n_q_heads > 65535 || t->n_kv_heads > 65535) return MLORA_ESHAPE;
+    if (t->n_q_heads / t->n_kv_heads > 8 || t->n_q_heads > 65535 || t->n_kv_heads > 65535) return MLORA_ESHAPE;
     if (t->n_streams <= 0 || t->rows_per_stream <= 0 || t->rows_per_stream > 64) return MLORA_ESHAPE;
     if ((long long)t->n_streams * t->rows_per_stream > MLORA_MAX_ROWS) return MLORA_ESHAPE;
     if (t->len_prefill < 0 || t->len_fprefix < 0 || t->cap_stream < 0) return MLORA_ESHAPE;
@@ -423,13 +450,13 @@ mlora_status mlora_tree_attention(const mlora_tree_attn *t, const void *q, void 
     const int per_slice = qv_per_slice(t->head_dim);
     const int slices = (a.M * a.G + per_slice - 1) / per_slice;   // (stream segments need fewer: their extra slices find no tile)
     const dim3 grid1((unsigned)items, (unsigned)a.Hkv, (unsigned)slices);
-    const dim3 grid2((unsigned)a.M, (unsigned)a.Hq);
+    const dim3 grid2((unsigned)a.M, (unsigned)a.Hkv);
     if (t->head_dim == 64) {
         tree_attn_partial<64><<<grid1, dim3(256), 0, s>>>(a);
-        tree_attn_combine<64><<<grid2, dim3(64), 0, s>>>(a);
+        tree_attn_combine<64><<<grid2, dim3(64 * a.G), 0, s>>>(a);
     } else {
         tree_attn_partial<128><<<grid1, dim3(256), 0, s>>>(a);
-        tree_attn_combine<128><<<grid2, dim3(128), 0, s>>>(a);
+        tree_attn_combine<128><<<grid2, dim3(128 * a.G), 0, s>>>(a);
     }
     return hipGetLastError() == hipSuccess ? MLORA_OK : MLORA_EHIP;
 }

@@ -207,7 +207,7 @@ def test_tree_attention_sizes_and_argument_checks():
 
     for bad in (dict(head_dim=96), dict(n_q_heads=7), dict(n_kv_heads=0), dict(rows_per_stream=65),
                 dict(rows_per_stream=0), dict(n_streams=0), dict(n_streams=2000), dict(len_prefill=-1),
-                dict(n_q_heads=64, n_kv_heads=2)):
+                dict(n_q_heads=36, n_kv_heads=2)):
         assert cdll.mlora_tree_attention_workspace_bytes(C.byref(tree_attn(**bad))) == 0
         assert call(tree_attn(**bad)) == ESHAPE
     for bad in (dict(k_new=None), dict(parent=None), dict(k_prefill=None), dict(v_fprefix=None), dict(len_stream=None)):
