@@ -1217,102 +1217,6 @@ struct WideLds {
     alignas(16) float stage[WIDE_TILES][16 * (TILE_N + 4)]; // per wave: 16 rows of outputs on their way out
 };
 
-struct WideRegs {
-    u32x4 w[4];
-    uint2 sc[4];
-};
-
-// Request super-step ss of the unit (n_ss super-steps; past the end: one 16-byte read of the first chunk).
-__device__ __forceinline__ void wide_request(WideRegs &r, const u32x4 *wp0, const uint2 *sp0, int ss, int n_ss,
-                                             int gs, int lane)
-{
-    const bool in = ss < n_ss;
-    const u32x4 *wn = wp0 + (in ? (size_t)ss * 256 + lane : 0);
-    const uint2 *sn = sp0 + (in ? (size_t)ss * gs * 16 + (lane & 15) : 0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) r.w[u] = __builtin_nontemporal_load(wn + (in ? u * 64 : 0));   // (read once)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) r.sc[g] = sn[in ? min(g, gs - 1) * 16 : 0];
-}
-
-// One super-step of the 64 x 64 tile; xs = this lane's fragment of row block 0, k-step 0 in the
-// LDS stage (row lane%16, 16 bytes number lane/16 of the k-step; indexed in units of 16 bytes:
-// a row block is XROW of them further, a k-step 4); prev = scale unit of acc per column block.
-template <int SPG>
-__device__ __forceinline__ void wide_math(f32x4 (&acc)[4][4], float (&prev)[4], const WideRegs &r,
-                                          const uint4 *xs, uint32_t mask, uint32_t bias)
-{
-    constexpr int GS = 4 / SPG;
-    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
-    constexpr uint32_t CODE0 = 0x88888888u;                // eight codes 0 (offset binary 8), before placing the fields
-    // the fragments of x of a group stay in registers for the offset term and the products
-    // alike when the group is short (up to 2 k-steps); longer groups read them twice
-    constexpr bool KEEP_X = SPG <= 2;
-#pragma unroll
-    for (int g = 0; g < GS; ++g) {
-        const uint2 sv = r.sc[g];
-        float ratio[4];
-        bool dead[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
-                           : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
-            dead[j] = sj == 0.f;
-            const float unit = dead[j] ? prev[j] : sj;     // (prev starts at 1: never zero)
-            // (one rounding per group, 2^-23 relative; the reciprocal is good to one unit in
-            // the last place, which a few dozen groups over K do not turn into anything visible)
-            ratio[j] = prev[j] * __builtin_amdgcn_rcpf(unit);
-            prev[j] = unit;
-        }
-
-        uint4 xk[KEEP_X ? SPG : 1][4];
-        if constexpr (KEEP_X) {
-#pragma unroll
-            for (int t = 0; t < SPG; ++t)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) xk[t][mb] = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
-        }
-        // offset term of the group: -24 * sum of x over its inputs, per row
-        f32x4 corr[4];
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-            corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < SPG; ++t) {
-                uint4 xa;
-                if constexpr (KEEP_X) xa = xk[t][mb];
-                else xa = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
-                corr[mb] = mfma16(xa, neg24, corr[mb]);
-            }
-        }
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(acc[mb][j][e], ratio[j], corr[mb][e]);
-#pragma unroll
-        for (int t = 0; t < SPG; ++t) {
-            uint4 xa[4];
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                if constexpr (KEEP_X) xa[mb] = xk[t][mb];
-                else xa[mb] = xs[mb * WideLds<4>::XROW + (g * SPG + t) * 4];
-            }
-            const u32x4 wv = r.w[g * SPG + t];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint32_t wj = j == 0 ? wv.x : j == 1 ? wv.y : j == 2 ? wv.z : wv.w;
-                // a dead column's codes become code 0 (the field layout is the same in every dword)
-                wj = dead[j] ? rotl32(CODE0, 3) : wj;
-                const uint4 wb = expand_codes(wj, mask, bias);
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) acc[mb][j] = mfma16(xa[mb], wb, acc[mb][j]);
-            }
-        }
-    }
-}
-
 // eight fp32 -> the bf16 A-operand fragments of their high and low halves
 __device__ __forceinline__ void split_bf16(const float (&v)[8], uint4 &hi, uint4 &lo)
 {
@@ -1327,33 +1231,38 @@ __device__ __forceinline__ void split_bf16(const float (&v)[8], uint4 &hi, uint4
 }
 
 // ------------------------------------------------------------------------------------------
-// 17 to 32 rows: the weight stream is what bounds the call, but the arithmetic per packed
-// byte (unpack, 8 + 2 MFMAs, 32 rescale FMAs per k-step) is close behind, so the K loop is as
-// plain as it can be made.  Per wave: the packed codes and the scales of the next 8 k-steps are
-// in registers (8 KiB in flight), each register set requested again as soon as its k-step is
-// consumed; the rows of x come through LDS in stages of 8 k-steps shared by the block's four
-// waves (one barrier per stage).  The scale multiplies the fp32 sum of a group, as everywhere.
+// The K loop of the wide blocks.  Per wave: the packed codes of the next 8 k-steps and their
+// scales are in registers (8 KiB in flight), each register set requested again as soon as its
+// k-step is consumed; the rows of x come through LDS in stages (8 k-steps of 32 rows, or 4
+// k-steps of 64 rows: 16 KiB, double-buffered, one barrier per stage) shared by the block's four
+// waves.  The codes enter the matrix units exactly; the scale multiplies the fp32 sum of a
+// group with plain fp32 FMAs (the cheapest vector instructions on this chip: integer and mixed
+// 16/32-bit operations issue at half their rate), so the loop is as short as the arithmetic
+// allows: per k-step 28 integer operations to unpack, 16 * MB FMAs per scale group, 4 * MB + MB
+// MFMAs.
 // ------------------------------------------------------------------------------------------
-template <int SPG>
-__device__ __forceinline__ void stream32_loop(f32x4 (&acc)[2][4], const u32x4 *wp, const uint2 *sp,
-                                              const unsigned char *const (&xrow)[4], int piece16, const int (&xdst)[4],
-                                              unsigned char *lds_x, const unsigned char *xfrag, int n_ksteps,
-                                              uint32_t mask, uint32_t bias)
+template <int SPG, int MB>
+__device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp, const uint2 *sp,
+                                            const unsigned char *const (&xrow)[4], int piece16, const int (&xdst)[4],
+                                            unsigned char *lds_x, const unsigned char *xfrag, int n_ksteps,
+                                            uint32_t mask, uint32_t bias)
 {
-    using L = WideLds<2>;
-    constexpr int S = L::XSTEPS;                           // k-steps per stage (and registers sets per wave)
-    static_assert(S % SPG == 0, "a stage holds whole scale groups");
+    using L = WideLds<MB>;
+    constexpr int S = L::XSTEPS;                           // k-steps per stage of x
+    constexpr int W = 8;                                   // k-steps of codes in registers
+    constexpr int HALVES = W / S;                          // stages per pass over the register sets
+    static_assert(S % SPG == 0 && W % S == 0, "a stage holds whole scale groups; the sets hold whole stages");
     const u32x4 neg24 = {0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u};
     const int last = n_ksteps - 1;
-    u32x4 w[S];
-    uint2 sc[S / SPG];
+    u32x4 w[W];
+    uint2 sc[W / SPG];
     u32x4 xr[4];
     // (requests past the unit's end re-read its last k-step: all loads stay unconditional)
     const int x_last = n_ksteps * 64 - 16;                 // last 16-byte piece of a row inside the unit
 #pragma unroll
     for (int i = 0; i < 4; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xrow[i] + min(piece16, x_last));
 #pragma unroll
-    for (int k = 0; k < S; ++k) {
+    for (int k = 0; k < W; ++k) {
         const int kc = min(k, last);
         w[k] = __builtin_nontemporal_load(wp + kc * 64);
         if (k % SPG == 0) sc[k / SPG] = sp[(kc / SPG) * 16];
@@ -1361,8 +1270,10 @@ __device__ __forceinline__ void stream32_loop(f32x4 (&acc)[2][4], const u32x4 *w
 #pragma unroll
     for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds_x + xdst[i]) = xr[i];
     const int n_stages = (n_ksteps + S - 1) / S;
-#pragma nounroll
-    for (int st = 0; st < n_stages; ++st) {
+
+    // one stage: register sets [h * S, h * S + S), x buffer st & 1
+    auto stage = [&](auto half, int st) {
+        constexpr int H = decltype(half)::value;
         __syncthreads();                                   // this stage's rows of x are in place; the other buffer is free
         const int buf = (st & 1) * L::X_STAGE;
         const int x_off = min(min(st + 1, n_stages - 1) * S * 64 + piece16, x_last);
@@ -1372,65 +1283,76 @@ __device__ __forceinline__ void stream32_loop(f32x4 (&acc)[2][4], const u32x4 *w
         // on an odd super-step): one straight piece of code, no branches inside
         auto stage_math = [&](auto nk) {
             constexpr int NK = decltype(nk)::value;
+            // A scale group is worked through in runs of SG = min(SPG, 2) k-steps: the run's
+            // fragments of x stay in registers for the offset term and for all four column
+            // blocks, and the products of one column block (MB accumulators of 16 x 16) are folded
+            // into acc as soon as the run is done, so few registers live at a time.  A group of 4
+            // k-steps is two runs that use the same scale.
+            constexpr int SG = SPG < 2 ? SPG : 2;
 #pragma unroll
-            for (int g = 0; g < NK / SPG; ++g) {
-                // the fragments of x of a group stay in registers for the offset term and the
-                // products alike when the group is short (up to 2 k-steps); longer groups read them twice
-                constexpr bool KEEP_X = SPG <= 2;
-                u32x4 xk[KEEP_X ? SPG : 1][2];
-                auto x_frag = [&](int k, int mb) {
-                    return *reinterpret_cast<const u32x4 *>(xfrag + buf + mb * 16 * L::XROW + k * 64);
-                };
-                // offset term of the group: -24 * sum of x over its inputs cancels the offset of the stored codes
-                f32x4 corr[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            for (int r = 0; r < NK / SG; ++r) {
+                u32x4 xk[SG][MB];
+                // offset term of the run: -24 * sum of x over its inputs cancels the offset of the stored codes
+                f32x4 corr[MB];
 #pragma unroll
-                for (int t = 0; t < SPG; ++t)
+                for (int mb = 0; mb < MB; ++mb) corr[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        const u32x4 xa = x_frag(g * SPG + t, mb);
-                        if constexpr (KEEP_X) xk[t][mb] = xa;
-                        corr[mb] = mfma16(__builtin_bit_cast(uint4, xa), __builtin_bit_cast(uint4, neg24), corr[mb]);
+                for (int t = 0; t < SG; ++t)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        xk[t][mb] = *reinterpret_cast<const u32x4 *>(xfrag + buf + mb * 16 * L::XROW + (r * SG + t) * 64);
+                        corr[mb] = mfma16(__builtin_bit_cast(uint4, xk[t][mb]), __builtin_bit_cast(uint4, neg24), corr[mb]);
                     }
-                f32x4 d[2][4];
+                u32x4 wv[SG];
 #pragma unroll
-                for (int t = 0; t < SPG; ++t) {
-                    const int k = g * SPG + t;
-                    u32x4 xa[2];
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        if constexpr (KEEP_X) xa[mb] = xk[t][mb];
-                        else xa[mb] = x_frag(k, mb);
-                    }
-                    const u32x4 wv = w[k];
-                    const int kc = min((st + 1) * S + k, last);
-                    w[k] = __builtin_nontemporal_load(wp + kc * 64);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint4 wb = expand_codes(wv[j], mask, bias);
-#pragma unroll
-                        for (int mb = 0; mb < 2; ++mb)
-                            d[mb][j] = mfma16(__builtin_bit_cast(uint4, xa[mb]), wb, t == 0 ? corr[mb] : d[mb][j]);
-                    }
+                for (int t = 0; t < SG; ++t) {
+                    const int k = r * SG + t;              // k-step within the stage
+                    wv[t] = w[H * S + k];
+                    const int kc = min(st * S + k + W, last);
+                    w[H * S + k] = __builtin_nontemporal_load(wp + kc * 64);
                 }
-                const uint2 sv = sc[g];
-                const int gc = min(((st + 1) * S + g * SPG), last) / SPG;
-                sc[g] = sp[gc * 16];
+                constexpr int G0 = (H * S) / SPG;          // first scale group of this stage's register sets
+                const int g = (r * SG) / SPG;              // scale group of the run within the stage
+                const uint2 sv = sc[G0 + g];
+                if ((r * SG + SG) % SPG == 0) {            // last run of its group: request the set's next group
+                    const int gc = min(st * S + g * SPG + W, last) / SPG;
+                    sc[G0 + g] = sp[gc * 16];
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
+                    f32x4 d[MB];
+#pragma unroll
+                    for (int t = 0; t < SG; ++t) {
+                        const uint4 wb = expand_codes(wv[t][j], mask, bias);
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+                            d[mb] = mfma16(__builtin_bit_cast(uint4, xk[t][mb]), wb, t == 0 ? corr[mb] : d[mb]);
+                    }
                     float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
                              : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
                     asm volatile("" : "+v"(sj));           // a float in a register: plain fp32 FMAs below
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][j][e], sj, acc[mb][j][e]);
+                        for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][e], sj, acc[mb][j][e]);
                 }
             }
         };
-        if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
-        else                        stage_math(std::integral_constant<int, 4>{});
+        if constexpr (S > 4) {
+            if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
+            else                        stage_math(std::integral_constant<int, 4>{});
+        } else {
+            stage_math(std::integral_constant<int, S>{});  // (a unit is a whole number of 4-k-step stages)
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds_x + (L::X_STAGE - buf) + xdst[i]) = xr[i];
+    };
+#pragma nounroll
+    for (int st = 0; st < n_stages; st += HALVES) {
+        stage(std::integral_constant<int, 0>{}, st);
+        if constexpr (HALVES == 2) {
+            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1);
+        }
     }
 }
 
@@ -1482,76 +1404,22 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if constexpr (MB == 2) {
-        // rows of x: thread t moves, per stage, the 16-byte pieces t + 256 i (i = 0..3) of the
-        // stage's 32 rows x 512 bytes
+    // rows of x: thread t moves, per stage, four 16-byte pieces: piece t % PPR of rows t / PPR + RPI * i
+    // (PPR pieces per row and stage, RPI rows per instruction of the block)
+    {
+        constexpr int PPR = L::XSTEPS * 4, RPI = 256 / PPR;
         const unsigned char *xrow[4];
         int xdst[4];
-        const int piece16 = (tid & 31) * 16;
+        const int piece16 = (tid % PPR) * 16;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = (tid >> 5) + 8 * i;
+            const int row = tid / PPR + RPI * i;
             xrow[i] = reinterpret_cast<const unsigned char *>(P.x + (size_t)(m0 + min(row, rows_here - 1)) * K +
                                                               (size_t)unit_beg * SUPER_K);
             xdst[i] = row * L::XROW + piece16;
         }
         const unsigned char *xfrag = lds.buf + l16 * L::XROW + lq * 16;
-        stream32_loop<SPG>(acc, wp + lane, sp + l16, xrow, piece16, xdst, lds.buf, xfrag, unit_cnt * 4, mask, bias);
-    } else {
-    // rows of x: thread t moves, per stage, 16 bytes of rows t/16 + 16*i (i = 0..3)
-    const uint16_t *xsrc[4];
-    int xdst[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 16 * i + (tid >> 4);
-        xsrc[i] = P.x + (size_t)(m0 + min(row, rows_here - 1)) * K + (size_t)unit_beg * SUPER_K + (tid & 15) * 8;
-        xdst[i] = row * L::XROW + (tid & 15) * 16;
-    }
-    const uint4 *xfrag = reinterpret_cast<const uint4 *>(lds.buf) + l16 * (L::XROW / 16) + lq;
-
-    float prev[4] = {1.f, 1.f, 1.f, 1.f};                  // unit of acc per column block (acc = 0: any unit will do)
-
-    WideRegs ra, rb;
-    u32x4 xr[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
-    wide_request(ra, wp, sp, 0, unit_cnt, gs, lane);
-    wide_request(rb, wp, sp, 1, unit_cnt, gs, lane);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + xdst[i]) = xr[i];
-
-    auto math = [&](const WideRegs &r, int stage) {
-        wide_math<SPG>(acc, prev, r, xfrag + stage * (L::X_STAGE / 16), mask, bias);
-    };
-#pragma nounroll
-    for (int ss = 0; ss < unit_cnt; ss += 2) {
-        // stage ss: set A, x buffer 0
-        __syncthreads();                                   // its rows of x are in place; buffer 1 is free
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)min(ss + 1, unit_cnt - 1) * SUPER_K);
-        math(ra, 0);
-        wide_request(ra, wp, sp, ss + 2, unit_cnt, gs, lane);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + L::X_STAGE + xdst[i]) = xr[i];
-
-        // stage ss + 1: set B, x buffer 1
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            xr[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)min(ss + 2, unit_cnt - 1) * SUPER_K);
-        if (ss + 1 < unit_cnt) math(rb, 1);
-        wide_request(rb, wp, sp, ss + 3, unit_cnt, gs, lane);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds.buf + xdst[i]) = xr[i];
-    }
-
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[mb][j][e] *= prev[j];
+        stream_loop<SPG, MB>(acc, wp + lane, sp + l16, xrow, piece16, xdst, lds.buf, xfrag, unit_cnt * 4, mask, bias);
     }
 
     // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
