@@ -330,15 +330,17 @@ def main():
         max_rel_err = max(max_rel_err, float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))))
     assert max_rel_err <= (2e-4 if args.y_fp32 else 5e-3), max_rel_err
 
-    # ---- the dominant (only) kernel: one launch per call
-    launches_per_step = calls_per_step * math.ceil((n_proj * w.layers // calls_per_step) / 128)
+    # ---- the dominant (only) kernel; which one and how many launches a call makes is asked of
+    # the library itself
+    info = lib.layer_step_plan(plans[0][0].keep[0], M)
+    launches_per_step = calls_per_step * info["launches"]
     n_ev = K * launches_per_step
     kern_s = ev_s / n_ev
     base_bytes = step_bytes / launches_per_step
     achieved = base_bytes / kern_s / 1e9
-    wide = M >= 33                       # the library's kernel for 33 rows and more
+    wide = info["wide"]
     spg = w.projs[0].group // 32
-    kernel_name = ("wide_kernel<%d>" % spg) if wide else \
+    kernel_name = ("wide_kernel<%d, %d>" % (spg, 2 if M <= 32 else 4)) if wide else \
         "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
     kernel_tag = "wide_kernel" if wide else "layer_kernel"
     achieved_tflops = (step_flops / launches_per_step) / kern_s / 1e12

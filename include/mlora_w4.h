@@ -124,6 +124,15 @@ mlora_status mlora_group_rows(const int32_t *row_adapter, int32_t M, int32_t n_a
  *    workspace has to be initialised again.  mlora_w4_workspace_status reads the word. */
 size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M);
 
+/* How a call over these projections and M rows would be run, for reading profiles; host only,
+ * nothing is launched.  info (HOST memory, 5 int32): [0] kernel launches of the call (one per
+ * 128 projections; from 17 rows on also a new one where the group size changes),
+ * [1] 1 if the first launch runs blocks of four column tiles ("wide_kernel"), 0 if blocks of
+ * one column tile ("layer_kernel"), [2] rows per row chunk (16, 32 or 64), [3] and [4] the
+ * first launch's grid: blocks along x, groups of 16 projections along z.
+ * MLORA_EINVAL for null pointers or n_proj <= 0, MLORA_ESHAPE for shapes the library refuses. */
+mlora_status mlora_w4_layer_step_plan(const mlora_w4_proj *projs, int32_t n_proj, int32_t M, int32_t *info);
+
 /* Zero-fill a workspace (a small kernel on `stream`; no memset node, so it can be captured). */
 mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 

@@ -16,7 +16,7 @@ exported_symbols = (
     "mlora_strerror", "mlora_w4_blob_bytes", "mlora_w4_prepack", "mlora_w4_unpack",
     "mlora_group_rows", "mlora_w4_workspace_bytes", "mlora_w4_linear", "mlora_w4_layer_step",
     "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
-    "mlora_w4_layer_step_static",
+    "mlora_w4_layer_step_static", "mlora_w4_layer_step_plan",
     "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
 )
 
@@ -179,6 +179,15 @@ def debug_spin_limit(limit: int) -> int:
 def workspace_bytes(projs: Sequence[Proj], M: int) -> int:
     arr = _proj_array(projs)
     return int(load_library().mlora_w4_workspace_bytes(arr, len(projs), M))
+
+
+def layer_step_plan(projs: Sequence[Proj], M: int) -> dict:
+    """How the library would run a call over these projections (see mlora_w4_layer_step_plan)."""
+    arr = _proj_array(projs)
+    info = (C.c_int32 * 5)()
+    _check(load_library().mlora_w4_layer_step_plan(arr, len(projs), M, info), "mlora_w4_layer_step_plan")
+    return {"launches": info[0], "wide": bool(info[1]), "rows_per_chunk": info[2],
+            "grid_x": info[3], "grid_z": info[4]}
 
 
 def linear(proj: Proj, x, row_adapter, M: int, y, y_dtype: int = Y_BF16, workspace=None) -> None:

@@ -356,6 +356,29 @@ size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int3
     return workspace_need(ctrl_total, data_total);
 }
 
+mlora_status mlora_w4_layer_step_plan(const mlora_w4_proj *projs, int32_t n_proj, int32_t M, int32_t *info)
+{
+    if (!projs || !info || n_proj <= 0) return MLORA_EINVAL;
+    if (M <= 0 || M > MLORA_MAX_ROWS) return MLORA_ESHAPE;
+    for (int i = 0; i < n_proj; ++i)
+        if (check_weight_shape(projs[i].K, projs[i].N, projs[i].group) != MLORA_OK) return MLORA_ESHAPE;
+    int launches = 0;
+    for (int first = 0, count = 0; first < n_proj; first += count, ++launches) {
+        count = launch_run(projs + first, n_proj - first, M);
+        LaunchNeed need;
+        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, true, need, nullptr, nullptr, nullptr);
+        if (st != MLORA_OK) return st;
+        if (first == 0) {
+            info[1] = launch_is_wide(projs, count, M) ? 1 : 0;
+            info[2] = rows_per_chunk(M);
+            info[3] = need.grid_x;
+            info[4] = need.groups;
+        }
+    }
+    info[0] = launches;
+    return MLORA_OK;
+}
+
 mlora_status mlora_w4_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace) return workspace_bytes == 0 ? MLORA_OK : MLORA_EINVAL;

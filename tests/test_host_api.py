@@ -93,6 +93,31 @@ def test_workspace_bytes():
     assert cdll.mlora_w4_workspace_bytes(C.byref(proj()), 1, 4097) == 0
 
 
+def test_layer_step_plan_names_the_kernel_family():
+    """Blocks of one column tile up to 16 rows and for short launches of 17 to 32 rows; blocks of
+    four column tiles from 33 rows on, and at 17 to 32 rows once a launch has 300 such blocks."""
+    cdll = lib.load_library()
+    info = (C.c_int32 * 5)()
+
+    def plan(arr, n, M):
+        assert cdll.mlora_w4_layer_step_plan(arr, n, M, info) == OK
+        return list(info)
+
+    one = (binding._ProjStruct * 1)(proj(K=2048, N=2048, rank=16))
+    assert plan(one, 1, 8)[:3] == [1, 0, 16]
+    assert plan(one, 1, 32)[:3] == [1, 0, 32]          # 8 blocks of four tiles: far below 300
+    assert plan(one, 1, 33)[:3] == [1, 1, 64]
+    many = (binding._ProjStruct * 130)(*[proj(K=2048, N=2048, rank=16) for _ in range(130)])
+    got = plan(many, 130, 32)                           # 128 + 2 projections: two launches
+    assert got[:3] == [2, 1, 32] and got[4] == 8
+    assert plan(many, 130, 16)[:3] == [2, 0, 16]
+    mixed = (binding._ProjStruct * 2)(proj(K=2048, group=32, rank=16), proj(K=2048, group=64, rank=16))
+    assert plan(mixed, 2, 16)[0] == 1 and plan(mixed, 2, 17)[0] == 2   # group size changes
+    assert cdll.mlora_w4_layer_step_plan(one, 1, 0, info) == ESHAPE
+    assert cdll.mlora_w4_layer_step_plan(one, 0, 8, info) == EINVAL
+    assert cdll.mlora_w4_layer_step_plan(one, 1, 8, None) == EINVAL
+
+
 def test_workspace_init_rejects_bad_arguments():
     cdll = lib.load_library()
     assert cdll.mlora_w4_workspace_init(None, 0, None) == OK
