@@ -18,6 +18,7 @@ exported_symbols = (
     "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
     "mlora_w4_layer_step_static", "mlora_w4_layer_step_plan",
     "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
+    "mlora_ds2d_rows", "mlora_ds2d_layout", "mlora_ds2d_workspace_bytes", "mlora_ds2d_step",
 )
 
 
@@ -31,6 +32,12 @@ class _ProjStruct(C.Structure):
     _fields_ = [("K", C.c_int32), ("N", C.c_int32), ("group", C.c_int32),
                 ("w_blob", C.c_void_p), ("n_adapters", C.c_int32), ("rank", C.c_int32),
                 ("lora_a", C.c_void_p), ("lora_b", C.c_void_p), ("alpha", C.c_float)]
+
+
+class _Ds2dStruct(C.Structure):
+    _fields_ = [("n_streams", C.c_int32), ("n_forecast", C.c_int32), ("depth", C.c_int32),
+                ("branch", C.c_int32 * 8), ("next_depth", C.c_int32), ("next_branch", C.c_int32 * 8),
+                ("vocab", C.c_int32), ("logits_dtype", C.c_int32)]
 
 
 class _TreeAttnStruct(C.Structure):
@@ -84,6 +91,16 @@ def load_library():
         lib.mlora_tree_attention_workspace_bytes.argtypes = [tp]
         lib.mlora_tree_attention.restype = C.c_int
         lib.mlora_tree_attention.argtypes = [tp, vp, vp, i32, vp, sz, vp]
+        dp = C.POINTER(_Ds2dStruct)
+        ip = C.POINTER(i32)
+        lib.mlora_ds2d_rows.restype = C.c_int
+        lib.mlora_ds2d_rows.argtypes = [ip, i32, i32, ip, ip]
+        lib.mlora_ds2d_layout.restype = C.c_int
+        lib.mlora_ds2d_layout.argtypes = [ip, i32, i32, ip, C.POINTER(C.c_uint8), ip]
+        lib.mlora_ds2d_workspace_bytes.restype = sz
+        lib.mlora_ds2d_workspace_bytes.argtypes = [dp]
+        lib.mlora_ds2d_step.restype = C.c_int
+        lib.mlora_ds2d_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.mlora_w4_workspace_status.restype = C.c_int
         lib.mlora_w4_workspace_status.argtypes = [vp, C.POINTER(i32), vp]
         lib.mlora_w4_debug_spin_limit.restype = i32
@@ -265,3 +282,48 @@ class TreeAttention:
         _check(load_library().mlora_tree_attention(C.byref(self.struct), _ptr(q), _ptr(out), out_dtype,
                                                    _ptr(workspace), n, _stream() if stream is None else stream),
                "mlora_tree_attention")
+
+
+def ds2d_rows(branch: Sequence[int], n_forecast: int):
+    """(tokens, rows) of one stream for a branch configuration (mlora_ds2d_rows)."""
+    arr = (C.c_int32 * max(1, len(branch)))(*[int(b) for b in branch])
+    t, r = C.c_int32(0), C.c_int32(0)
+    _check(load_library().mlora_ds2d_rows(arr, len(branch), n_forecast, C.byref(t), C.byref(r)), "mlora_ds2d_rows")
+    return int(t.value), int(r.value)
+
+
+def ds2d_layout(branch: Sequence[int], n_forecast: int):
+    """(parent, is_forecast, level) lists of one stream (mlora_ds2d_layout)."""
+    _, rows = ds2d_rows(branch, n_forecast)
+    arr = (C.c_int32 * max(1, len(branch)))(*[int(b) for b in branch])
+    parent, level = (C.c_int32 * rows)(), (C.c_int32 * rows)()
+    is_forecast = (C.c_uint8 * rows)()
+    _check(load_library().mlora_ds2d_layout(arr, len(branch), n_forecast, parent, is_forecast, level),
+           "mlora_ds2d_layout")
+    return list(parent), list(is_forecast), list(level)
+
+
+class Ds2dStep:
+    """Descriptor of mlora_ds2d_step (include/mlora_ds2d.h)."""
+
+    def __init__(self, n_streams: int, n_forecast: int, branch: Sequence[int], next_branch: Sequence[int],
+                 vocab: int, logits_dtype: int):
+        st = _Ds2dStruct()
+        st.n_streams, st.n_forecast, st.depth, st.next_depth = n_streams, n_forecast, len(branch), len(next_branch)
+        for i, b in enumerate(branch):
+            st.branch[i] = int(b)
+        for i, b in enumerate(next_branch):
+            st.next_branch[i] = int(b)
+        st.vocab, st.logits_dtype = vocab, logits_dtype
+        self.struct = st
+
+    def workspace_bytes(self) -> int:
+        return int(load_library().mlora_ds2d_workspace_bytes(C.byref(self.struct)))
+
+    def run(self, logits, tokens, n_accepted, accepted_rows, emitted, next_tokens, workspace,
+            stream: Optional[int] = None) -> None:
+        n = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(load_library().mlora_ds2d_step(C.byref(self.struct), _ptr(logits), _ptr(tokens), _ptr(n_accepted),
+                                              _ptr(accepted_rows), _ptr(emitted), _ptr(next_tokens),
+                                              _ptr(workspace), n, _stream() if stream is None else stream),
+               "mlora_ds2d_step")

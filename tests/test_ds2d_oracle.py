@@ -15,28 +15,38 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
 def golden_counts():
-    out = {}
+    """The counts the paper states for its worked example, and the branch configurations of its
+    Table 7 (tests/golden/ds2d_worked_example.txt)."""
+    out, table7 = {}, []
     for line in open(os.path.join(GOLDEN, "ds2d_worked_example.txt")):
         if line.startswith("#") or not line.strip():
             continue
-        key, *vals = line.split()
-        out[key] = [int(v) for v in vals]
-    return out
+        key, value = line.split()
+        vals = [int(v) for v in value.split(",")]
+        if key == "table7":
+            table7.append(tuple(vals))
+        else:
+            out[key] = vals
+    return out, table7
 
 
 def test_worked_example_counts():
-    g = golden_counts()
-    m, branch = g["forecast_embeddings"][0], g["branch"]
+    g, table7 = golden_counts()
+    m, branch = g["m"][0], g["branch"]
     parent, is_forecast, level = ds2d.tree_rows(branch, m)
     n_tok = ds2d.n_tokens(branch)
-    assert n_tok == g["tokens_in_step_2"][0]
+    assert n_tok == g["tokens"][0]
     assert n_tok - 1 == g["draft_tokens"][0]
-    assert int(is_forecast.sum()) == g["forecast_rows_in_step_2"][0]
-    assert len(parent) == g["rows_in_step_2"][0]
-    assert int(((level == 1) & (is_forecast == 0)).sum()) == g["first_level_drafts"][0]
+    assert int(is_forecast.sum()) == g["forecast_embeddings"][0]
+    assert len(parent) == g["rows"][0]
+    assert int(((level == 1) & (is_forecast == 0)).sum()) == branch[0]
     # the first step has no drafts: the last prompt token and its forecast embeddings
     p1, f1, _ = ds2d.tree_rows((), m)
     assert list(p1) == [-1, 0, 1] and list(f1) == [0, 1, 1]
+    # every configuration of Table 7 fits the row budget the paper fixes
+    for cfg in table7:
+        rows = len(ds2d.tree_rows(cfg, len(cfg))[0])
+        assert rows == ds2d.n_tokens(cfg) * (1 + len(cfg)) <= g["row_budget"][0]
 
 
 def test_tree_rows_against_the_input_generators_layout_and_the_hand_written_depths():
@@ -153,8 +163,8 @@ def test_tokens_given_out_equal_plain_greedy_decoding(branch, quality):
 
 
 def test_new_drafts_come_from_the_node_where_the_walk_ended_and_from_nowhere_else():
-    g = golden_counts()
-    m, branch = g["forecast_embeddings"][0], tuple(g["branch"])
+    g, _ = golden_counts()
+    m, branch = g["m"][0], tuple(g["branch"])
     rng = np.random.default_rng(3)
     n_tok = ds2d.n_tokens(branch)
     logits = rng.standard_normal((n_tok * (1 + m), V))
@@ -165,7 +175,9 @@ def test_new_drafts_come_from_the_node_where_the_walk_ended_and_from_nowhere_els
     tokens[6], tokens[7] = 20, 21
     logits[2, 20] = 50.0
     res = ds2d.step(branch, branch, m, logits, tokens)
-    assert res["accepted_rows"] == [0, 2, 6] and len(res["accepted_rows"]) == g["accepted_path_nodes"][0]
+    # (the paper's figure has three tokens accepted in a row -- the root, a first-level and a
+    # second-level draft -- and the new drafts taken from the last of them)
+    assert res["accepted_rows"] == [0, 2, 6]
     assert res["emitted"][:2] == [2, 20] and res["emitted"][2] == int(np.argmax(logits[6]))
     rows = [n_tok + 6 * m, n_tok + 6 * m + 1]
     top1 = list(np.argsort(-logits[rows[0]], kind="stable")[:3])

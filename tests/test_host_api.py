@@ -16,7 +16,7 @@ OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE = 0, -1, -2, -3, -4
 
 def header_functions():
     names = set()
-    for header in ("mlora_w4.h", "mlora_tree_attention.h"):
+    for header in ("mlora_w4.h", "mlora_tree_attention.h", "mlora_ds2d.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(mlora_[a-z0-9_]+)\s*\(", text))
@@ -247,3 +247,40 @@ def test_tree_attention_sizes_and_argument_checks():
     assert call(t, ws_bytes=want - 1) == EWORKSPACE
     assert call(t, ws=0xE010) == EALIGN
     assert cdll.mlora_tree_attention(None, 1, 1, 0, 1, 1, None) == EINVAL
+
+
+def test_ds2d_rows_layout_and_argument_checks():
+    """Host side of the DS2D step: row counts of the paper's worked example (Section 3.5: m = 2,
+    branch (3, 2): 10 tokens, 30 rows; first step 1 + m rows), the layout against the input
+    generators' own, and the descriptor checks (nothing is launched)."""
+    import numpy as np
+    from workloads.attention import ds2d_tree
+    assert lib.ds2d_rows((3, 2), 2) == (10, 30)
+    assert lib.ds2d_rows((), 2) == (1, 3)
+    assert lib.ds2d_rows((2,), 3) == (3, 12)
+    for branch in [(3, 2), (2, 2, 2), (4,), (1, 1, 1)]:
+        parent, is_forecast, level = lib.ds2d_layout(branch, len(branch))
+        p2, f2 = ds2d_tree(branch)
+        assert parent == list(p2) and is_forecast == list(f2)
+    parent, is_forecast, level = lib.ds2d_layout((3, 2), 2)
+    assert level[:10] == [0, 1, 1, 1, 2, 2, 2, 2, 2, 2] and level[10:14] == [1, 2, 1, 2]
+    with pytest.raises(lib.MloraError):
+        lib.ds2d_rows((3, 2, 4), 3)                  # 1 + 3 + 6 + 24 tokens x 4 rows > 64
+    with pytest.raises(lib.MloraError):
+        lib.ds2d_rows((3, 2), 1)                     # more levels than forecast embeddings
+    with pytest.raises(lib.MloraError):
+        lib.ds2d_rows((17,), 1)
+    d = lib.Ds2dStep(2, 2, (3, 2), (3, 2), 1000, lib.Y_BF16)
+    # 2 streams x 30 rows x 1 slice of 4096 logits x 16 keys of 8 bytes
+    assert d.workspace_bytes() == 2 * 30 * 1 * 16 * 8
+    assert lib.Ds2dStep(1, 2, (3, 2), (3, 2), 128256, lib.Y_BF16).workspace_bytes() == 30 * 32 * 16 * 8
+    assert lib.Ds2dStep(1, 2, (3, 2), (3, 2), 2, lib.Y_BF16).workspace_bytes() == 0     # vocab < b'
+    assert lib.Ds2dStep(0, 2, (3, 2), (3, 2), 100, lib.Y_BF16).workspace_bytes() == 0
+    assert lib.Ds2dStep(1, 2, (3, 2), (3, 2), 100, 7).workspace_bytes() == 0
+    cdll = lib.load_library()
+    fn = cdll.mlora_ds2d_step
+    st = C.byref(d.struct)
+    assert fn(st, None, 16, 16, 16, 16, 16, 16, 1 << 20, None) == EINVAL
+    assert fn(st, 8, 16, 16, 16, 16, 16, 16, 1 << 20, None) == EALIGN
+    assert fn(st, 16, 16, 16, 16, 16, 16, 16, 100, None) == EWORKSPACE
+    assert fn(st, 16, 16, 16, 16, 16, 16, None, 0, None) == EWORKSPACE
