@@ -45,10 +45,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4_decode",
-                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down, c4_attention")
+                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down, c4_attention, c4_ds2d")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
                          "eager: one library call per step from Python")
+    ap.add_argument("--streams", type=int, default=1, help="output streams of the c4_ds2d workload")
     ap.add_argument("--copies", type=int, default=0, help="rotating copies (0 = enough to defeat the cache)")
     ap.add_argument("--per-layer-calls", action="store_true",
                     help="one library call (one launch) per layer instead of one per step")
@@ -71,6 +72,105 @@ def measured_traffic(kernel_tag: str, workload: str):
         return None, None
     m = re.search(r"hbm_traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read())
     return (int(m.group(1)), os.path.relpath(path, ROOT)) if m else (None, None)
+
+
+def bench_ds2d(args):
+    """--workload c4_ds2d: the token side of a DS2D step (verification of the draft tree and
+    drafting of the next one) on the logits of one stream of the paper's worked example: 30 rows
+    (branch (3, 2), two forecast embeddings) of 128256 bf16 logits."""
+    import numpy as np
+    import torch
+
+    import paper_2604_18655_amd as lib
+    from oracle import ds2d as oracle_ds2d
+    from workloads.ds2d import make_ds2d_inputs
+    from workloads.generate import bf16_bits_to_f32
+
+    lib.load_library()
+    torch.cuda.set_device(0)
+    S, m, branch, V = args.streams, 2, (3, 2), 128256
+    T, R = lib.ds2d_rows(branch, m)
+    call_bytes = S * R * V * 2
+    copies = args.copies or (3 * CACHE_BYTES + call_bytes - 1) // call_bytes
+    d = lib.Ds2dStep(S, m, branch, branch, V, lib.Y_BF16)
+    t0 = time.time()
+    logits0, tokens0 = make_ds2d_inputs(0, S, branch, m, V, True, accept=0.8)
+    sets = []
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    for c in range(copies):
+        if c == 0:
+            lg = torch.from_numpy(logits0.view(np.int16)).cuda()
+            tk = torch.from_numpy(tokens0).cuda()
+        else:
+            lg = (torch.randn((S * R, V), generator=gen, device="cuda") * 2.0).to(torch.bfloat16)
+            tk = torch.randint(0, V, (S, T), generator=gen, device="cuda", dtype=torch.int32)
+        outs = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in (S, S * (m + 1), S * (m + 1), S * T)]
+        ws = torch.empty(d.workspace_bytes(), dtype=torch.uint8, device="cuda")
+        sets.append((lg, tk, outs, ws))
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def run_step(i, stream=None):
+        lg, tk, outs, ws = sets[i % copies]
+        d.run(lg, tk, outs[0], outs[1], outs[2], outs[3], ws, stream)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(K):
+                run_step(args.warmup + i, side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev0.record()
+    graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    call_s = ev0.elapsed_time(ev1) * 1e-3 / K
+
+    # copy 0 against the oracle: every output is an integer and must match exactly
+    ref = oracle_ds2d.step(branch, branch, m, bf16_bits_to_f32(logits0[:R]).astype(np.float64), tokens0[0])
+    outs = [o.cpu().numpy() for o in sets[0][2]]
+    a = len(ref["accepted_rows"]) - 1
+    assert int(outs[0][0]) == a and list(outs[1][:a + 1]) == ref["accepted_rows"]
+    assert list(outs[2][:a + 1]) == ref["emitted"] and list(outs[3][:T]) == ref["next_tokens"]
+    gbs = call_bytes / (elapsed / K) / 1e9
+    result = {
+        "metric": "µs per DS2D verify-and-draft step + achieved HBM GB/s (% of 8 TB/s), 1 MI355X",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / K, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_ds2d: verification and drafting on the logits of one DS2D step",
+                   "streams": S, "branch": list(branch), "forecast_embeddings": m, "rows": R, "vocab": V,
+                   "rotating_copies": int(copies), "launch_mode": "graph"},
+        "us_per_step": round(elapsed * 1e6 / K, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "algorithmic_bytes_per_step": call_bytes, "oracle_match": "exact", "setup_s": round(setup_s, 1),
+        "roofline": {"kernel": "ds2d_best_partial<bf16> + ds2d_verify_draft (one call)", "bound": "hbm",
+                     "achieved": round(call_bytes / call_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(call_bytes / call_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(call_bytes), "avg_launch_us": round(call_s * 1e6, 3),
+                     "launches_timed": K,
+                     "timed_with": "two HIP events around the timed region on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 10.0:
+            oracle_ds2d.step(branch, branch, m, bf16_bits_to_f32(logits0[:R]).astype(np.float64), tokens0[0])
+            n += 1
+        dt = (time.perf_counter() - t0) / n
+        result["cpu_baseline"] = {"value": round(call_bytes / S / dt / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                  "kind": "oracle", "sample": f"{n} steps of one stream of the same workload, {dt:.2f} s each"}
+    print(json.dumps(result))
 
 
 def bench_attention(args):
@@ -191,6 +291,9 @@ def main():
         print("bench.py: this build runs on one GPU only (the path shards along N, see DESIGN.md); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "c4_ds2d":
+        bench_ds2d(args)
+        return
     if args.workload == "c4_attention":
         bench_attention(args)
         return

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/mlora_ds2d.h"
 
 namespace mlora {
@@ -83,10 +85,54 @@ __device__ inline int wanted(const Ds2dArgs &a, int r)
     return j < a.next_depth ? a.next_branch[j] : 0;
 }
 
+// 32-bit keys for bf16 logits: a bf16 value orders by 16 bits, which leaves room for the position
+// inside the block's slice (4096 logits): (sortable value << 16) | (0xFFFF - position).  Lower
+// positions are lower token ids, so these keys order a slice exactly like the 64-bit ones; they
+// are widened when the winners are stored.
+__device__ inline unsigned key16_of(unsigned h, unsigned pos)
+{
+    unsigned hi;
+    if ((h & 0x7FFFu) > 0x7F80u) hi = 0u;                              // NaN
+    else {
+        if (h == 0x8000u) h = 0u;                                      // -0 counts as +0
+        hi = (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u);
+    }
+    return (hi << 16) | (0xFFFFu - pos);
+}
+template <int N>
+__device__ __forceinline__ unsigned ror_u32(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x120 + N, 0xF, 0xF, false);
+}
+// the largest value over the block: rows of 16 lanes by DPP rotations, the 16 rows through LDS
+// (`slot` is 2 x 16 words, alternated by `phase`)
+__device__ inline unsigned block_max(unsigned v, unsigned *slot, int phase)
+{
+    unsigned o;
+    o = ror_u32<8>(v); v = o > v ? o : v;
+    o = ror_u32<4>(v); v = o > v ? o : v;
+    o = ror_u32<2>(v); v = o > v ? o : v;
+    o = ror_u32<1>(v); v = o > v ? o : v;
+    unsigned *s = slot + (phase & 1) * 16;
+    if ((threadIdx.x & 15) == 0) s[threadIdx.x >> 4] = v;
+    __syncthreads();
+    const uint4 *q = reinterpret_cast<const uint4 *>(s);
+    unsigned r = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 t = q[i];
+        const unsigned m0 = t.x > t.y ? t.x : t.y, m1 = t.z > t.w ? t.z : t.w;
+        const unsigned m = m0 > m1 ? m0 : m1;
+        r = m > r ? m : r;
+    }
+    return r;
+}
+
 template <bool FP32>
 __global__ __launch_bounds__(DS_THREADS) void ds2d_best_partial(const Ds2dArgs a)
 {
-    __shared__ unsigned long long slot[8];
+    using Key = typename std::conditional<FP32, unsigned long long, unsigned>::type;
+    __shared__ __align__(16) Key slot[32];
     const int row = blockIdx.y;
     const int k = wanted(a, row % a.R);
     if (k == 0) return;
@@ -99,57 +145,67 @@ __global__ __launch_bounds__(DS_THREADS) void ds2d_best_partial(const Ds2dArgs a
     const long long first = (long long)row * a.V, last = first + a.V;
     const long long vec0 = first / EPV + (long long)blockIdx.x * (DS_THREADS * VPT);
     const long long full_vectors = a.total / EPV;
-    unsigned long long key[DS_ELEMS];
+    const long long slice_first = vec0 * EPV;                           // element at position 0
+    // the row's part of this slice, as positions 0 .. DS_SLICE, and the token id at pos_lo
+    const int pos_lo = first > slice_first ? (int)(first - slice_first) : 0;
+    const int pos_hi = last - slice_first < DS_SLICE ? (last > slice_first ? (int)(last - slice_first) : 0) : DS_SLICE;
+    const unsigned token_lo = (unsigned)(slice_first + pos_lo - first);
+    Key key[DS_ELEMS];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
         const long long vi = vec0 + (long long)u * DS_THREADS + threadIdx.x;
         const long long e0 = vi * EPV;
-        float f[EPV];
+        const unsigned pos0 = (unsigned)(u * DS_THREADS + threadIdx.x) * EPV;
+        unsigned bits[EPV];                     // fp32 patterns, or bf16 patterns in the low half
         if (e0 >= last) {
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) f[j] = 0.f;
+            for (int j = 0; j < EPV; ++j) bits[j] = 0u;
         } else if (vi < full_vectors) {
+            const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.logits) + vi);
             if constexpr (FP32) {
-                const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.logits) + vi);
-                f[0] = q.x; f[1] = q.y; f[2] = q.z; f[3] = q.w;
+                bits[0] = q.x; bits[1] = q.y; bits[2] = q.z; bits[3] = q.w;
             } else {
-                const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.logits) + vi);
-                const unsigned w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    f[2 * j] = __uint_as_float(w[j] << 16);
-                    f[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
-                }
+                bits[0] = q.x & 0xFFFFu; bits[1] = q.x >> 16; bits[2] = q.y & 0xFFFFu; bits[3] = q.y >> 16;
+                bits[4] = q.z & 0xFFFFu; bits[5] = q.z >> 16; bits[6] = q.w & 0xFFFFu; bits[7] = q.w >> 16;
             }
         } else {
 #pragma unroll
             for (int j = 0; j < EPV; ++j) {
-                f[j] = 0.f;
+                bits[j] = 0u;
                 if (e0 + j < a.total) {
-                    if constexpr (FP32) f[j] = reinterpret_cast<const float *>(a.logits)[e0 + j];
-                    else f[j] = bf16_value(reinterpret_cast<const unsigned short *>(a.logits)[e0 + j]);
+                    if constexpr (FP32) bits[j] = reinterpret_cast<const unsigned *>(a.logits)[e0 + j];
+                    else bits[j] = reinterpret_cast<const unsigned short *>(a.logits)[e0 + j];
                 }
             }
         }
 #pragma unroll
         for (int j = 0; j < EPV; ++j) {
-            const long long e = e0 + j;
-            key[u * EPV + j] = (e >= first && e < last) ? key_of(f[j], (unsigned)(e - first)) : 0ull;
+            const int pos = (int)pos0 + j;                  // inside the row iff pos_lo <= pos < pos_hi
+            const bool inside = pos >= pos_lo && pos < pos_hi;
+            if constexpr (FP32) key[u * EPV + j] = inside ? key_of(__uint_as_float(bits[j]), (unsigned)(pos - pos_lo) + token_lo) : 0ull;
+            else key[u * EPV + j] = inside ? key16_of(bits[j], (unsigned)pos) : 0u;
         }
     }
     unsigned long long *out = a.partial + ((size_t)row * a.slices + blockIdx.x) * DS_KMAX;
-    unsigned long long below = ~0ull;
+    Key below = ~(Key)0;
     for (int round = 0; round < k; ++round) {
-        unsigned long long best = 0ull;
+        Key best = 0;
 #pragma unroll
         for (int u = 0; u < DS_ELEMS; ++u) {
-            const unsigned long long c = key[u] < below ? key[u] : 0ull;
+            const Key c = key[u] < below ? key[u] : (Key)0;
             best = c > best ? c : best;
         }
         best = block_max(best, slot, round);
-        if (threadIdx.x == 0) out[round] = best;
+        if (threadIdx.x == 0) {
+            if constexpr (FP32) out[round] = best;
+            else {
+                // widen: the value's 16 bits on top, the complement of the token id below
+                const unsigned token = (unsigned)(slice_first + (long long)(0xFFFFu - (best & 0xFFFFu)) - first);
+                out[round] = best == 0u ? 0ull : ((unsigned long long)(best >> 16) << 48) | (unsigned long long)(~token);
+            }
+        }
         below = best;
-        if (best == 0ull) {                      // the slice holds fewer than k logits
+        if (best == 0) {                         // the slice holds fewer than k logits
             for (int r2 = round + 1 + (int)threadIdx.x; r2 < k; r2 += DS_THREADS) out[r2] = 0ull;
             break;
         }
@@ -160,26 +216,39 @@ __global__ __launch_bounds__(DS_THREADS) void ds2d_verify_draft(const Ds2dArgs a
 {
     __shared__ unsigned long long slot[8];
     __shared__ unsigned long long best_key[MLORA_DS2D_MAX_ROWS];
+    __shared__ int tok[MLORA_DS2D_MAX_ROWS];
     __shared__ int walk_end, walk_token;
-    __shared__ int cand[DS_KMAX];
-    const int s = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    __shared__ int cand[MLORA_DS2D_MAX_FORECAST][DS_KMAX];
+    const int s = blockIdx.x, tid = threadIdx.x;
 
-    // arg-max of every token row: the best of the first keys of its slices
-    for (int r = wave; r < a.T; r += DS_THREADS / 64) {
-        const unsigned long long *p = a.partial + ((size_t)(s * a.R + r) * a.slices) * DS_KMAX;
-        unsigned long long v = 0ull;
-        for (int sl = lane; sl < a.slices; sl += 64) {
-            const unsigned long long c = p[(size_t)sl * DS_KMAX];
-            v = c > v ? c : v;
+    // arg-max of every token row: the best of the first keys of its slices.  All (row, slice)
+    // pairs are spread over the block, so the loads are independent of each other.
+    if (tid < a.T) {
+        best_key[tid] = 0ull;
+        tok[tid] = a.tokens[(size_t)s * a.T + tid];
+    }
+    __syncthreads();
+    const unsigned long long *base = a.partial + (size_t)s * a.R * a.slices * DS_KMAX;
+    // (loads are issued in batches of eight before any of them is used: a loop that stores each
+    // value as it arrives would wait for memory once per element)
+    constexpr int BATCH = 8;
+    for (int i0 = 0; i0 < a.T * a.slices; i0 += BATCH * DS_THREADS) {
+        unsigned long long v[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int i = i0 + u * DS_THREADS + tid;                          // row * slices + slice
+            v[u] = i < a.T * a.slices ? base[(size_t)i * DS_KMAX] : 0ull;
         }
-        v = wave_max(v);
-        if (lane == 0) best_key[r] = v;
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int i = i0 + u * DS_THREADS + tid;
+            if (i < a.T * a.slices) atomicMax(&best_key[i / a.slices], v[u]);
+        }
     }
     __syncthreads();
 
-    // the walk (one thread; the tree has at most 64 tokens and 8 levels)
+    // the walk (one thread; the tree has at most 64 tokens and 8 levels; everything is in LDS)
     if (tid == 0) {
-        const int32_t *tok = a.tokens + (size_t)s * a.T;
         int32_t *rows = a.accepted_rows + (size_t)s * (a.m + 1);
         int32_t *out = a.emitted + (size_t)s * (a.m + 1);
         int cur = 0, n = 0;
@@ -208,30 +277,55 @@ __global__ __launch_bounds__(DS_THREADS) void ds2d_verify_draft(const Ds2dArgs a
     int32_t *nt = a.next_tokens + (size_t)s * a.T_next;
     if (tid == 0) nt[0] = walk_token;
 
-    // level i of the next tree: the b'_i best of forecast embedding i of the node `cur`
-    int offset = 1, width = 1, phase = 0;
-    for (int i = 0; i < a.next_depth; ++i) {
+    // Level i of the next tree: the b'_i best of forecast embedding i of the node `cur`.  A
+    // thread keeps its share of a level's candidates in registers (two each: up to 512
+    // candidates, e.g. 32 slices x 16; what lies beyond is read again every round), and the loads
+    // of all levels are issued before the first round.
+    constexpr int OWN = 2;
+    unsigned long long own[MLORA_DS2D_MAX_FORECAST][OWN];
+#pragma unroll
+    for (int i = 0; i < MLORA_DS2D_MAX_FORECAST; ++i) {
+        if (i >= a.next_depth) break;
         const int b = a.next_branch[i];
-        const int row = a.T + cur * a.m + i;
-        const unsigned long long *p = a.partial + ((size_t)(s * a.R + row) * a.slices) * DS_KMAX;
+        const unsigned long long *p = base + (size_t)(a.T + cur * a.m + i) * a.slices * DS_KMAX;
+#pragma unroll
+        for (int u = 0; u < OWN; ++u) {
+            const int c = tid + u * DS_THREADS;
+            own[i][u] = c < a.slices * b ? p[(size_t)(c / b) * DS_KMAX + (c % b)] : 0ull;
+        }
+    }
+    int phase = 0;
+#pragma unroll
+    for (int i = 0; i < MLORA_DS2D_MAX_FORECAST; ++i) {
+        if (i >= a.next_depth) break;
+        const int b = a.next_branch[i];
+        const unsigned long long *p = base + (size_t)(a.T + cur * a.m + i) * a.slices * DS_KMAX;
         const int n_cand = a.slices * b;
         unsigned long long below = ~0ull;
         for (int round = 0; round < b; ++round) {
             unsigned long long v = 0ull;
-            for (int c = tid; c < n_cand; c += DS_THREADS) {
+#pragma unroll
+            for (int u = 0; u < OWN; ++u) {
+                const unsigned long long q = own[i][u] < below ? own[i][u] : 0ull;
+                v = q > v ? q : v;
+            }
+            for (int c = tid + OWN * DS_THREADS; c < n_cand; c += DS_THREADS) {
                 unsigned long long q = p[(size_t)(c / b) * DS_KMAX + (c % b)];
                 q = q < below ? q : 0ull;
                 v = q > v ? q : v;
             }
             v = block_max(v, slot, phase++);
-            if (tid == 0) cand[round] = (int)(~(unsigned)(v & 0xFFFFFFFFull));
+            if (tid == 0) cand[i][round] = (int)(~(unsigned)(v & 0xFFFFFFFFull));
             below = v;
         }
-        __syncthreads();
+    }
+    __syncthreads();
+    int offset = 1, width = 1;
+    for (int i = 0; i < a.next_depth; ++i) {
+        const int b = a.next_branch[i];
         width *= b;
-        for (int q = tid; q < width; q += DS_THREADS) nt[offset + q] = cand[q % b];
+        for (int q = tid; q < width; q += DS_THREADS) nt[offset + q] = cand[i][q % b];
         offset += width;
-        __syncthreads();
     }
 }
 
