@@ -529,6 +529,21 @@ def main():
                       f"{t_cpu:.1f} s of fp64 loops on {cores} threads",
             "us_per_linear": round(t_cpu / reps / len(probs0) * 1e6, 1),
         }
+        if w.key in ("c1", "c2", "c3"):
+            # the small configurations also on ONE host thread (bounded the same way)
+            oracle.set_threads(1)
+            reps1, t1_cpu = 0, 0.0
+            while t1_cpu < 10.0 and reps1 < 1000:
+                t1 = time.perf_counter()
+                for p, x in zip(probs0, xs0):
+                    oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows_h)
+                t1_cpu += time.perf_counter() - t1
+                reps1 += 1
+            oracle.set_threads(cores)
+            result["cpu_baseline"]["single_thread"] = {
+                "value": round(layer_bytes * reps1 / t1_cpu / 1e9, 4), "unit": "GB/s", "cores": 1,
+                "us_per_linear": round(t1_cpu / reps1 / len(probs0) * 1e6, 1),
+                "sample": f"the same layer, {reps1} repetitions, {t1_cpu:.1f} s on 1 thread"}
     print(json.dumps(result, ensure_ascii=False), flush=True)
 
 
