@@ -14,7 +14,8 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "oracle.c"), os.path.join(_HERE, "tree_attention.c")]
+_SRCS = [os.path.join(_HERE, "oracle.c"), os.path.join(_HERE, "tree_attention.c"),
+         os.path.join(_HERE, "act_quant.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -52,6 +53,11 @@ def _load():
         lib.orc_max_threads.restype = i32
         lib.orc_linear.argtypes = [i32, i32, i32, u8p, u16p, i32, i32, u16p, u16p, C.c_double,
                                    u16p, i32p, i32, f64p, f64p]
+        lib.orc_linear_a8.argtypes = [i32, i32, i32, u8p, u16p, i32, u16p, u16p, C.c_double,
+                                      i8p, C.c_double, i32p, i32, f64p]
+        lib.orc_linear_a8.restype = None
+        lib.orc_quantise_act.argtypes = [f32p, C.c_size_t, i8p]
+        lib.orc_quantise_act.restype = C.c_float
         lib.orc_tree_attention.restype = i32
         lib.orc_tree_attention.argtypes = [i32, i32, i32, i32, i32, C.c_double,
                                            u16p, u16p, i32, u16p, u16p, i32, u16p, u16p, i32, i32p,
@@ -167,6 +173,38 @@ def linear(wq, scales, group, lora_a, lora_b, alpha, x, row_adapter, return_t: b
                        _p(x, C.c_uint16), None if ra is None else _p(ra, C.c_int32), M,
                        _p(y, C.c_double), _p(t, C.c_double))
     return (y, t) if return_t else y
+
+
+def linear_a8(wq, scales, group, lora_a, lora_b, alpha, xq, x_scale, row_adapter):
+    """y[M][N] in float64 for one projection on int8 activations xq [M][K] with scale x_scale
+    (act_quant.c)."""
+    wq, scales = _arr(wq, np.uint8), _arr(scales, np.uint16)
+    lora_a, lora_b = _arr(lora_a, np.uint16), _arr(lora_b, np.uint16)
+    xq = _arr(xq, np.int8)
+    N, K = wq.shape[0], wq.shape[1] * 2
+    M = xq.shape[0]
+    n_adapters, rank = lora_a.shape[0], lora_a.shape[1]
+    assert xq.shape == (M, K) and scales.shape == (N, K // group)
+    assert lora_a.shape == (n_adapters, rank, K) and lora_b.shape == (n_adapters, N, rank)
+    ra = None if row_adapter is None else _arr(row_adapter, np.int32)
+    if ra is not None:
+        assert ra.shape == (M,)
+        if ra.size and (ra.min() < -1 or ra.max() >= n_adapters):
+            raise ValueError("row_adapter index outside [-1, n_adapters)")
+    y = np.empty((M, N), np.float64)
+    _load().orc_linear_a8(K, N, group, _p(wq, C.c_uint8), _p(scales, C.c_uint16), rank,
+                          _p(lora_a, C.c_uint16), _p(lora_b, C.c_uint16), float(alpha),
+                          _p(xq, C.c_int8), float(x_scale), None if ra is None else _p(ra, C.c_int32), M,
+                          _p(y, C.c_double))
+    return y
+
+
+def quantise_act(x):
+    """(xq int8, scale float32) of a float32 tensor: one scale per tensor (act_quant.c)."""
+    x = _arr(x, np.float32)
+    xq = np.empty(x.shape, np.int8)
+    scale = _load().orc_quantise_act(_p(x, C.c_float), x.size, _p(xq, C.c_int8))
+    return xq, np.float32(scale)
 
 
 def tree_attention(q, k_prefill, v_prefill, k_fprefix, v_fprefix, k_stream, v_stream, len_stream,

@@ -88,6 +88,22 @@ def make_x(M: int, K: int, cfg_id: int, layer: int, slot_index: int) -> np.ndarr
     return f32_to_bf16_bits(x)
 
 
+def quantise_act_int8(x: np.ndarray) -> Tuple[np.ndarray, np.float32]:
+    """Per-tensor symmetric int8 quantisation of activations (Section 3.3 of the paper): one
+    scale max|x| / 127 in float32 (1 for an all-zero tensor), round to nearest even, clamp."""
+    x = np.asarray(x, np.float32)
+    top = np.float32(np.max(np.abs(x))) if x.size else np.float32(0)
+    scale = np.float32(top / np.float32(127.0)) if top > 0 else np.float32(1.0)
+    q = np.clip(np.rint(x / scale), -127, 127).astype(np.int8)
+    return q, scale
+
+
+def make_x_int8(M: int, K: int, cfg_id: int, layer: int, slot_index: int) -> Tuple[np.ndarray, np.float32]:
+    """The same N(0, 1) rows as make_x, quantised to int8 with one scale for the tensor."""
+    x = _rng(cfg_id, layer, slot_index, T_X).standard_normal((M, K), dtype=np.float32)
+    return quantise_act_int8(x)
+
+
 def make_rows(row_map: str, M: int, n_adapters: int, cfg_id: int = 0) -> np.ndarray:
     """Row -> adapter index (int32 [M]).
 
