@@ -147,6 +147,26 @@ mlora_status mlora_w4_workspace_status(const void *workspace, int32_t *status_wo
  * Process-wide, read when a call is enqueued.  Returns the previous value. */
 int32_t mlora_w4_debug_spin_limit(int32_t limit);
 
+/* The layer step with int8 activations (Section 3.3: activations quantised to int8 with one
+ * scale per tensor, weights to int4).  As mlora_w4_layer_step, except that
+ *   xs[i]        int8 [M][K]: the quantised rows; the activation they stand for is
+ *                x_scales[i] * xs[i][m][k]
+ *   x_scales     HOST array of n_proj floats, each finite and > 0 (a per-tensor scale is fixed
+ *                offline, by calibration or quantisation-aware training: it is an input here)
+ * and the result is that of Eq. 1-4 on those activations:
+ *   y[m] = x_scale * ( sum_g scale[n][g] * sum_{k in g} code[n][k] * xq[m][k]
+ *                      + alpha * B[a(m)] . (A[a(m)] . xq[m]) ).
+ * The inner sums run on the int8 matrix units and are exact in int32; scales are applied in
+ * fp32.  LoRA tensors stay bf16 (the paper's int16 LoRA is not built).  The weight blob is the
+ * one mlora_w4_prepack writes.  Every row count runs the blocks of four column tiles; size the
+ * workspace with mlora_w4a8_workspace_bytes (same layout and rules as mlora_w4_workspace_bytes).
+ * Errors as mlora_w4_layer_step, plus MLORA_EINVAL for a null, non-positive or non-finite scale. */
+size_t mlora_w4a8_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M);
+mlora_status mlora_w4a8_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                   const void *const *xs, const float *x_scales, void *const *ys,
+                                   const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* One projection.
  *   x            bf16 [M][K]
  *   row_adapter  int32 [M], -1 = no adapter for that row; NULL = no adapter for any row

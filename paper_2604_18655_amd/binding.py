@@ -18,6 +18,7 @@ exported_symbols = (
     "mlora_w4_workspace_init", "mlora_w4_workspace_status", "mlora_w4_debug_spin_limit",
     "mlora_w4_layer_step_static", "mlora_w4_layer_step_plan",
     "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
+    "mlora_w4a8_workspace_bytes", "mlora_w4a8_layer_step",
     "mlora_ds2d_rows", "mlora_ds2d_layout", "mlora_ds2d_workspace_bytes", "mlora_ds2d_step",
 )
 
@@ -91,6 +92,11 @@ def load_library():
         lib.mlora_tree_attention_workspace_bytes.argtypes = [tp]
         lib.mlora_tree_attention.restype = C.c_int
         lib.mlora_tree_attention.argtypes = [tp, vp, vp, i32, vp, sz, vp]
+        lib.mlora_w4a8_workspace_bytes.restype = sz
+        lib.mlora_w4a8_workspace_bytes.argtypes = [pp, i32, i32]
+        lib.mlora_w4a8_layer_step.restype = C.c_int
+        lib.mlora_w4a8_layer_step.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(C.c_float), C.POINTER(vp), vp,
+                                              i32, i32, vp, sz, vp]
         dp = C.POINTER(_Ds2dStruct)
         ip = C.POINTER(i32)
         lib.mlora_ds2d_rows.restype = C.c_int
@@ -238,6 +244,36 @@ class LayerPlan:
                      self.ws, self.ws_bytes, _stream() if stream is None else stream)
         if st != 0:
             raise MloraError(st, "mlora_w4_layer_step")
+
+
+def a8_workspace_bytes(projs: Sequence[Proj], M: int) -> int:
+    arr = _proj_array(projs)
+    return int(load_library().mlora_w4a8_workspace_bytes(arr, len(projs), M))
+
+
+class LayerPlanA8:
+    """Marshalled arguments of mlora_w4a8_layer_step (int8 activations, one scale per tensor)."""
+
+    def __init__(self, projs: Sequence[Proj], xs: Sequence, x_scales: Sequence[float], ys: Sequence,
+                 row_adapter, M: int, y_dtype: int, workspace):
+        assert len(projs) == len(xs) == len(ys) == len(x_scales)
+        self.keep = (list(projs), list(xs), list(ys), row_adapter, workspace)
+        self.n = len(projs)
+        self.arr = _proj_array(projs)
+        self.xs = (C.c_void_p * self.n)(*[_ptr(x) for x in xs])
+        self.ys = (C.c_void_p * self.n)(*[_ptr(y) for y in ys])
+        self.scales = (C.c_float * self.n)(*[float(v) for v in x_scales])
+        self.rows = _ptr(row_adapter)
+        self.M, self.y_dtype = int(M), int(y_dtype)
+        self.ws = _ptr(workspace)
+        self.ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self.fn = load_library().mlora_w4a8_layer_step
+
+    def run(self, stream: Optional[int] = None) -> None:
+        st = self.fn(self.arr, self.n, self.xs, self.scales, self.ys, self.rows, self.M, self.y_dtype,
+                     self.ws, self.ws_bytes, _stream() if stream is None else stream)
+        if st != 0:
+            raise MloraError(st, "mlora_w4a8_layer_step")
 
 
 def layer_step_static(projs: Sequence[Proj], xs: Sequence, ys: Sequence, row_adapter, M: int,

@@ -82,6 +82,9 @@ size_t t_part_bytes(const mlora_w4_proj &p, int M)
     return round_up((size_t)kch_of(p, M) * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256);
 }
 
+// Calls with int8 activations run wide blocks whatever their row count, and those work on chunks
+// of at least 32 rows with grouped shrink blocks: such a call is laid out as for 17 rows or more.
+int plan_rows(int M, bool a8) { return a8 && M < WIDE32_MIN_ROWS ? WIDE32_MIN_ROWS : M; }
 int m_pad_of(int M) { return (M + rows_per_chunk(M) - 1) / rows_per_chunk(M) * rows_per_chunk(M); }
 
 // K units per column tile.  Tile blocks: units of at most 2048 inputs (16 super-steps: what a
@@ -117,9 +120,9 @@ int launch_blocks_of(const mlora_w4_proj *projs, int count, int M, bool wide)
     return n;
 }
 // Which family of base blocks a launch over these projections runs (see common.hpp).
-bool launch_is_wide(const mlora_w4_proj *projs, int count, int M)
+bool launch_is_wide(const mlora_w4_proj *projs, int count, int M, bool a8)
 {
-    if (M >= WIDE_ALWAYS_ROWS) return true;
+    if (a8 || M >= WIDE_ALWAYS_ROWS) return true;
     if (M < WIDE32_MIN_ROWS) return false;
     return launch_blocks_of(projs, count, M, true) >= WIDE32_MIN_BLOCKS;
 }
@@ -209,11 +212,11 @@ struct LaunchNeed {
 };
 
 static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *xs, void *const *ys,
-                                int count, int M, bool lora_on, LaunchNeed &need, LayerArgs *a,
-                                char *ctrl, char *data)
+                                int count, int M, bool a8, bool lora_on, LaunchNeed &need, LayerArgs *a,
+                                char *ctrl, char *data, const float *x_scales = nullptr)
 {
     const int chunks = m_pad_of(M) / rows_per_chunk(M);
-    const bool wide = launch_is_wide(projs, count, M);
+    const bool wide = launch_is_wide(projs, count, M, a8);
     const int lb = launch_blocks_of(projs, count, M, wide);
     const int groups = (count + GROUP_PROJ - 1) / GROUP_PROJ;
     bool shared = false;                       // anything handed from block to block?
@@ -242,7 +245,7 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
             const size_t part_bytes = partial_bytes(p, M, wide, lb);
             const size_t t_bytes = lora ? t_part_bytes(p, M) : 0;
             const int n_shrink = !lora ? 0
-                : (M <= 16 ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *
+                : (M <= 16 && !wide ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *
                       (r16_of(p) / 16) * kch_of(p, M);
             if (a) {
                 ProjArgs &d = a->p[i];
@@ -256,6 +259,7 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
                 d.N = p.N;
                 d.spg = p.group / KSTEP;
                 d.alpha = p.alpha;
+                d.x_scale = x_scales ? x_scales[i] : 1.0f;
                 d.ksplit = ksplit;
                 // blocks (wide kernel: waves) that wait for this projection's shrink blocks: the
                 // finishing ones, or every K unit where the LoRA term is spread over them
@@ -318,13 +322,13 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
 
 // Sizes of a whole call (all its launches).
 static mlora_status plan_call(const mlora_w4_proj *projs, int n_proj, int M, bool lora_on,
-                              size_t &ctrl_total, size_t &data_total)
+                              size_t &ctrl_total, size_t &data_total, bool a8 = false)
 {
     ctrl_total = data_total = 0;
     for (int first = 0, count = 0; first < n_proj; first += count) {
         count = launch_run(projs + first, n_proj - first, M);
         LaunchNeed need;
-        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, lora_on, need, nullptr, nullptr, nullptr);
+        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, a8, lora_on, need, nullptr, nullptr, nullptr);
         if (st != MLORA_OK) return st;
         ctrl_total += need.ctrl_bytes;
         data_total += need.data_bytes;
@@ -366,10 +370,10 @@ mlora_status mlora_w4_layer_step_plan(const mlora_w4_proj *projs, int32_t n_proj
     for (int first = 0, count = 0; first < n_proj; first += count, ++launches) {
         count = launch_run(projs + first, n_proj - first, M);
         LaunchNeed need;
-        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, true, need, nullptr, nullptr, nullptr);
+        const mlora_status st = plan_launch(projs + first, nullptr, nullptr, count, M, false, true, need, nullptr, nullptr, nullptr);
         if (st != MLORA_OK) return st;
         if (first == 0) {
-            info[1] = launch_is_wide(projs, count, M) ? 1 : 0;
+            info[1] = launch_is_wide(projs, count, M, false) ? 1 : 0;
             info[2] = rows_per_chunk(M);
             info[3] = need.grid_x;
             info[4] = need.groups;
@@ -432,27 +436,31 @@ static mlora_status check_call(const mlora_w4_proj *projs, int32_t n_proj, const
 static mlora_status enqueue_call(const mlora_w4_proj *projs, int32_t n_proj, const void *const *xs,
                                  void *const *ys, const int32_t *row_adapter, int32_t M, int32_t y_dtype,
                                  bool lora_on, char *workspace, size_t workspace_bytes, size_t data_total,
-                                 hipStream_t s)
+                                 hipStream_t s, const float *x_scales = nullptr)
 {
+    const bool a8 = x_scales != nullptr;
+    const int Mp = plan_rows(M, a8);
     char *ctrl = workspace ? workspace + WS_HEADER_BYTES : nullptr;
     char *data = workspace ? workspace + workspace_bytes / 256 * 256 - round_up(data_total, 256) : nullptr;
     // (one argument block on the heap: it is about 19 KiB and is copied by the launch)
     std::unique_ptr<LayerArgs> a(new LayerArgs);
     for (int first = 0, count = 0; first < n_proj; first += count) {
-        count = launch_run(projs + first, n_proj - first, M);
+        count = launch_run(projs + first, n_proj - first, Mp);
         memset(a.get(), 0, sizeof(LayerArgs));
         a->row_adapter = lora_on ? row_adapter : nullptr;
         a->n_proj = count;
         a->M = M;
+        a->M_plan = Mp;
+        a->a8 = a8;
         a->y_fp32 = (y_dtype == MLORA_Y_FP32);
-        a->m_pad = m_pad_of(M);
+        a->m_pad = m_pad_of(Mp);
         a->spin_limit = g_spin_limit;
         a->code_mask = 0x00780078u;
         a->code_bias = 0x41804180u;
         a->status = reinterpret_cast<unsigned *>(workspace);
         LaunchNeed need;
-        const mlora_status st = plan_launch(projs + first, xs + first, ys + first, count, M, lora_on, need,
-                                            a.get(), ctrl, data);
+        const mlora_status st = plan_launch(projs + first, xs + first, ys + first, count, Mp, a8, lora_on, need,
+                                            a.get(), ctrl, data, x_scales ? x_scales + first : nullptr);
         if (st != MLORA_OK) return st;         // (cannot happen: the sizing pass has seen the same shapes)
         if (launch_layer(*a, need.grid_x, need.groups, s) != hipSuccess) return MLORA_EHIP;
         ctrl += need.ctrl_bytes;
@@ -510,6 +518,42 @@ mlora_status mlora_w4_layer_step_static(const mlora_w4_proj *projs, int32_t n_pr
     for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
     return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
                         ws, STATIC_SCRATCH_BYTES, data_total, (hipStream_t)stream);
+}
+
+size_t mlora_w4a8_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M)
+{
+    if (!projs || n_proj <= 0 || M <= 0 || M > MLORA_MAX_ROWS) return 0;
+    for (int i = 0; i < n_proj; ++i)
+        if (check_weight_shape(projs[i].K, projs[i].N, projs[i].group) != MLORA_OK) return 0;
+    size_t ctrl_total, data_total;
+    if (plan_call(projs, n_proj, plan_rows(M, true), true, ctrl_total, data_total, true) != MLORA_OK) return 0;
+    return workspace_need(ctrl_total, data_total);
+}
+
+mlora_status mlora_w4a8_layer_step(const mlora_w4_proj *projs, int32_t n_proj,
+                                   const void *const *xs, const float *x_scales, void *const *ys,
+                                   const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    mlora_status st = check_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype);
+    if (st != MLORA_OK) return st;
+    if (!x_scales) return MLORA_EINVAL;
+    for (int i = 0; i < n_proj; ++i)
+        if (!(x_scales[i] > 0.0f) || !(x_scales[i] < 3.0e38f)) return MLORA_EINVAL;     // also refuses NaN
+    if (M == 0) return MLORA_OK;
+    size_t ctrl_total, data_total;
+    st = plan_call(projs, n_proj, plan_rows(M, true), true, ctrl_total, data_total, true);
+    if (st != MLORA_OK) return st;
+    const size_t need = workspace_need(ctrl_total, data_total);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return MLORA_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
+    }
+    bool any_lora = false;
+    for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
+    return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
+                        need > 0 ? reinterpret_cast<char *>(workspace) : nullptr, workspace_bytes, data_total,
+                        (hipStream_t)stream, x_scales);
 }
 
 mlora_status mlora_w4_linear(const mlora_w4_proj *p, const void *x, const int32_t *row_adapter,

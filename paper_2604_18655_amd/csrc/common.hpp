@@ -77,6 +77,7 @@ struct ProjArgs {
     int r16;                   // rank rounded up to a multiple of 16
     int kch;                   // number of K chunks of the shrink step
     float alpha;
+    float x_scale;             // int8 activations: the per-tensor scale of x (1 otherwise)
     int ksplit;                // K units per tile; unit 0 finishes the tile, the others run ahead
     int n_shrink_blocks;       // shrink blocks of this projection (each bumps its counter once)
     int n_finish_blocks;       // finishing blocks of this projection (tiles x row chunks)
@@ -119,6 +120,10 @@ struct LayerArgs {
     const int *row_adapter;    // may be null
     int n_proj;
     int M;
+    int M_plan;                // the row count the launch was laid out for (chunk size, shrink
+                               // blocks): M, except that calls with int8 activations always run
+                               // wide blocks and are laid out as for at least 17 rows
+    int a8;                    // x is int8 with one scale per tensor (ProjArgs::x_scale)
     int y_fp32;
     int m_pad;                 // M rounded up to whole row chunks of the base kernel
     int spin_limit;            // polls a block makes before it gives up waiting (0: gives up at once)
@@ -151,6 +156,15 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 // of B at inputs 8*(l/16)..+7, and receives D[4*(l/16) + r][l%16] in element r.
 __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+
+// D[16][16] (int32) += A[16][32] * B[32][16] over int8; lane l supplies 8 bytes of row l%16 of A
+// and of column l%16 of B, both for the same 8 inputs (block l/16 of the 32), and receives
+// D[4*(l/16) + r][l%16] in element r.  Which byte stands for which input inside a lane's 8 does
+// not matter as long as A and B agree.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ inline i32x4 mfma16_i8(long a, long b, i32x4 c) {
+    return __builtin_amdgcn_mfma_i32_16x16x32_i8(a, b, c, 0, 0, 0);
 }
 
 // The grouped shrink step (more than 16 rows) works on chunks of 64 rows: the rows of a chunk are

@@ -884,13 +884,14 @@ struct ShrinkLds {
     alignas(16) unsigned char x[4][16 * ROW];
 };
 
+template <bool A8>
 __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs &P, int pi, int local, ShrinkLds &lds)
 {
     using L = ShrinkLds;
     constexpr int SB = L::SB;
     GroupLds64 &g = lds.g;
     const int jblocks = P.r16 / 16;
-    const int shares = shrink_tile_shares(a.M, P.n_adapters);
+    const int shares = shrink_tile_shares(a.M_plan, P.n_adapters);
     const int kc = local % P.kch;
     const int jb = (local / P.kch) % jblocks;
     const int share = (local / (P.kch * jblocks)) % shares;
@@ -926,7 +927,10 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
                 const int rr = 4 * i + lq;                  // staged row: tile row of x, rank row of A
                 x_ok[i] = rr < rows_here;
                 const int row = m_base + (x_ok[i] ? (int)g.perm[first + rr] : 0);
-                xsrc[i] = P.x + (size_t)row * P.K + (size_t)blk_beg * KSTEP + l16 * 8;
+                // (int8 rows: the same element offsets, one byte each; kept as a uint16 pointer and
+                // turned into a byte address where it is used)
+                xsrc[i] = A8 ? reinterpret_cast<const uint16_t *>(reinterpret_cast<const unsigned char *>(P.x) + (size_t)row * P.K + (size_t)blk_beg * KSTEP + l16 * 8)
+                             : P.x + (size_t)row * P.K + (size_t)blk_beg * KSTEP + l16 * 8;
                 const int j = jb * 16 + rr;
                 a_ok[i] = j < P.rank;
                 asrc[i] = P.lora_a + ((size_t)adapter * P.rank + (a_ok[i] ? j : 0)) * P.K + (size_t)blk_beg * KSTEP + l16 * 8;
@@ -939,7 +943,23 @@ __device__ __forceinline__ void shrink_block(const LayerArgs &a, const ProjArgs 
                 const bool k_ok = (l16 >> 2) < blk_cnt - s0;    // this lane's 8 inputs lie in k-step s0 + l16/4
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    xv[set][i] = (x_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)s0 * KSTEP) : zero;
+                    if constexpr (A8) {
+                        // eight int8 -> eight bf16 (exact: seven bits and a sign)
+                        uint2 q = make_uint2(0u, 0u);
+                        if (x_ok[i] && k_ok) q = *reinterpret_cast<const uint2 *>(reinterpret_cast<const unsigned char *>(xsrc[i]) + (size_t)s0 * KSTEP);
+                        const uint32_t src2[2] = {q.x, q.y};
+                        u32x4 o;
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            const uint32_t word = src2[h >> 1];
+                            const int e0 = (int)(signed char)(word >> (16 * (h & 1)));
+                            const int e1 = (int)(signed char)(word >> (16 * (h & 1) + 8));
+                            o[h] = (__float_as_uint((float)e0) >> 16) | (__float_as_uint((float)e1) & 0xFFFF0000u);
+                        }
+                        xv[set][i] = o;
+                    } else {
+                        xv[set][i] = (x_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)s0 * KSTEP) : zero;
+                    }
                     av[set][i] = (a_ok[i] && k_ok) ? *reinterpret_cast<const u32x4 *>(asrc[i] + (size_t)s0 * KSTEP) : zero;
                 }
             };
@@ -1160,7 +1180,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
         const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
         // (the instances with one block of 16 rows are the ones launched for M <= 16)
         if constexpr (MB == 1) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
-        else                   shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        else                   shrink_block<false>(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     const BaseLdsOf<MB, XR> lds{smem};
@@ -1356,10 +1376,144 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same K loop for int8 activations (one scale per tensor): the matrix units multiply int8 by
+// int8 into int32, so a scale group's sum is exact without any offset term.
+//  * Codes: the blob stores offset-binary nibbles u = code + 8 at bits 3, 7, ... of a dword (see
+//    common.hpp).  Flipping the top bit of every nibble turns them into two's complement, and a
+//    nibble in the upper half of a byte is the int8 number 16 * code:  t = w ^ 0x44444444,
+//    rotl(t, 1) & 0xF0F0F0F0 holds the codes of inputs 0, 4, 1, 5 of the lane's eight,
+//    rotl(t, 5) & 0xF0F0F0F0 those of inputs 7, 2, 6, 3: five integer operations for 8 weights.
+//    The factor 16 is taken out after the loop.
+//  * x: the bytes of a row are put into that same order (0, 4, 1, 5, 7, 2, 6, 3 within every
+//    eight) when a stage is written to LDS, so a lane's fragment is one 8-byte read.
+//  * int32 -> fp32 without a conversion: the accumulator of a run starts at 0x4B400000, the bit
+//    pattern of 1.5 * 2^23, so the int32 result, read as a float, is 12582912 + sum exactly
+//    (|sum| <= 2 * 32 * 128 * 127 < 2^22); one fp32 subtraction and one FMA with the group's scale
+//    follow, both at the full fp32 rate.
+// A stage holds the same k-steps as in the bf16 loop; its rows are half as long.
+// ------------------------------------------------------------------------------------------
+template <int MB>
+struct WideLdsA8 {
+    static constexpr int XSTEPS = WideLds<MB>::XSTEPS;
+    static constexpr int XROW = XSTEPS * 32 + 16;          // bytes of a row of x per stage (int8)
+};
+
+template <int SPG, int MB>
+__device__ __forceinline__ void stream_loop_a8(f32x4 (&acc)[MB][4], const u32x4 *wp, const uint2 *sp,
+                                               const unsigned char *const (&xrow)[2], int piece16, const int (&xdst)[2],
+                                               unsigned char *lds_x, const unsigned char *xfrag, int n_ksteps)
+{
+    using L = WideLds<MB>;
+    using L8 = WideLdsA8<MB>;
+    constexpr int S = L::XSTEPS;
+    constexpr int W = 8;
+    constexpr int HALVES = W / S;
+    const int last = n_ksteps - 1;
+    u32x4 w[W];
+    uint2 sc[W / SPG];
+    u32x4 xr[2];
+    const int x_last = n_ksteps * 32 - 16;                 // last 16-byte piece of a row inside the unit
+    // bytes (0,1,2,3 | 4,5,6,7) of every eight -> (0,4,1,5 | 7,2,6,3)
+    auto shuffled = [](u32x4 v) {
+        u32x4 o;
+        o[0] = __builtin_amdgcn_perm(v[1], v[0], 0x05010400u);
+        o[1] = __builtin_amdgcn_perm(v[1], v[0], 0x03060207u);
+        o[2] = __builtin_amdgcn_perm(v[3], v[2], 0x05010400u);
+        o[3] = __builtin_amdgcn_perm(v[3], v[2], 0x03060207u);
+        return o;
+    };
+#pragma unroll
+    for (int i = 0; i < 2; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xrow[i] + min(piece16, x_last));
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        const int kc = min(k, last);
+        w[k] = __builtin_nontemporal_load(wp + kc * 64);
+        if (k % SPG == 0) sc[k / SPG] = sp[(kc / SPG) * 16];
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(lds_x + xdst[i]) = shuffled(xr[i]);
+    const int n_stages = (n_ksteps + S - 1) / S;
+    const i32x4 magic = {0x4B400000, 0x4B400000, 0x4B400000, 0x4B400000};
+
+    auto stage = [&](auto half, int st) {
+        constexpr int H = decltype(half)::value;
+        __syncthreads();
+        const int buf = (st & 1) * L::X_STAGE;
+        const int x_off = min(min(st + 1, n_stages - 1) * S * 32 + piece16, x_last);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xrow[i] + x_off);
+        auto stage_math = [&](auto nk) {
+            constexpr int NK = decltype(nk)::value;
+            constexpr int SG = SPG < 2 ? SPG : 2;
+#pragma unroll
+            for (int r = 0; r < NK / SG; ++r) {
+                long xk[SG][MB];
+#pragma unroll
+                for (int t = 0; t < SG; ++t)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        xk[t][mb] = *reinterpret_cast<const long *>(xfrag + buf + mb * 16 * L8::XROW + (r * SG + t) * 32);
+                u32x4 wv[SG];
+#pragma unroll
+                for (int t = 0; t < SG; ++t) {
+                    const int k = r * SG + t;
+                    wv[t] = w[H * S + k] ^ 0x44444444u;
+                    const int kc = min(st * S + k + W, last);
+                    w[H * S + k] = __builtin_nontemporal_load(wp + kc * 64);
+                }
+                constexpr int G0 = (H * S) / SPG;
+                const int g = (r * SG) / SPG;
+                const uint2 sv = sc[G0 + g];
+                if ((r * SG + SG) % SPG == 0) {
+                    const int gc = min(st * S + g * SPG + W, last) / SPG;
+                    sc[G0 + g] = sp[gc * 16];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    i32x4 d[MB];
+#pragma unroll
+                    for (int t = 0; t < SG; ++t) {
+                        const uint32_t v = wv[t][j];
+                        const uint32_t hi = __builtin_amdgcn_alignbit(v, v, 31) & 0xF0F0F0F0u;
+                        const uint32_t lo = __builtin_amdgcn_alignbit(v, v, 27) & 0xF0F0F0F0u;
+                        const long wb = (long)(((unsigned long long)lo << 32) | hi);
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) d[mb] = mfma16_i8(xk[t][mb], wb, t == 0 ? magic : d[mb]);
+                    }
+                    float sj = j == 0 ? half_bits_lo(sv.x) : j == 1 ? half_bits_hi(sv.x)
+                             : j == 2 ? half_bits_lo(sv.y) : half_bits_hi(sv.y);
+                    asm volatile("" : "+v"(sj));
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            acc[mb][j][e] = fmaf(__int_as_float(d[mb][e]) - 12582912.0f, sj, acc[mb][j][e]);
+                }
+            }
+        };
+        if constexpr (S > 4) {
+            if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
+            else                        stage_math(std::integral_constant<int, 4>{});
+        } else {
+            stage_math(std::integral_constant<int, S>{});
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(lds_x + (L::X_STAGE - buf) + xdst[i]) = shuffled(xr[i]);
+    };
+#pragma nounroll
+    for (int st = 0; st < n_stages; st += HALVES) {
+        stage(std::integral_constant<int, 0>{}, st);
+        if constexpr (HALVES == 2) {
+            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1);
+        }
+    }
+}
+
 // group = index of the block's four tiles among the projection's; ku as in base_unit.  SPG =
 // k-steps per scale group, the same for every projection of the launch; MB = blocks of 16 rows
 // per chunk (2: calls of 17 to 32 rows, 4: 33 rows and more).
-template <int SPG, int MB>
+template <int SPG, int MB, bool A8>
 __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P, int pi, int group, int ku,
                                           int m0, WideLds<MB> &lds)
 {
@@ -1405,8 +1559,9 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // rows of x: thread t moves, per stage, four 16-byte pieces: piece t % PPR of rows t / PPR + RPI * i
-    // (PPR pieces per row and stage, RPI rows per instruction of the block)
-    {
+    // (PPR pieces per row and stage, RPI rows per instruction of the block); int8 rows are half as
+    // long: two pieces per thread
+    if constexpr (!A8) {
         constexpr int PPR = L::XSTEPS * 4, RPI = 256 / PPR;
         const unsigned char *xrow[4];
         int xdst[4];
@@ -1420,6 +1575,27 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         }
         const unsigned char *xfrag = lds.buf + l16 * L::XROW + lq * 16;
         stream_loop<SPG, MB>(acc, wp + lane, sp + l16, xrow, piece16, xdst, lds.buf, xfrag, unit_cnt * 4, mask, bias);
+    } else {
+        using L8 = WideLdsA8<MB>;
+        constexpr int PPR = L::XSTEPS * 2, RPI = 256 / PPR;
+        const unsigned char *xrow[2];
+        int xdst[2];
+        const int piece16 = (tid % PPR) * 16;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = tid / PPR + RPI * i;
+            xrow[i] = reinterpret_cast<const unsigned char *>(P.x) + (size_t)(m0 + min(row, rows_here - 1)) * K +
+                      (size_t)unit_beg * SUPER_K;
+            xdst[i] = row * L8::XROW + piece16;
+        }
+        const unsigned char *xfrag = lds.buf + l16 * L8::XROW + lq * 8;
+        stream_loop_a8<SPG, MB>(acc, wp + lane, sp + l16, xrow, piece16, xdst, lds.buf, xfrag, unit_cnt * 4);
+        // the codes went in as 16 * code, x as integers: one factor for both
+        const float f = P.x_scale * 0.0625f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[mb][j] *= f;
     }
 
     // One pass per (32 ranks, adapter that occurs in the chunk): its rows of B for the
@@ -1525,6 +1701,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
         // four neighbouring ranks (16 bytes) at a time; requests go out in batches of 4 such
         // quads x 4 chunks so that the round trips overlap.
         const int qpr = r32 / 4;                           // quads per row of t
+        const float t_factor = A8 ? P.alpha * P.x_scale : P.alpha;   // (the shrink blocks saw x as integers)
         for (int i0 = 0; i0 < ROWS * qpr; i0 += 4 * 256) {
             f32x4_t v[4];
 #pragma unroll
@@ -1556,7 +1733,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                 const int ml = idx / qpr, jj = (idx % qpr) * 4;
                 const bool live = ml < rows_here && jj < P.r16;
                 if (ml < ROWS)
-                    *reinterpret_cast<f32x4_t *>(tl + ml * L::T_STRIDE + jj) = live ? v[q] * P.alpha : f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4_t *>(tl + ml * L::T_STRIDE + jj) = live ? v[q] * t_factor : f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
         __syncthreads();
@@ -1715,7 +1892,7 @@ constexpr int wide_lds_bytes()
     return sizeof(WideLds<MB>) > sizeof(ShrinkLds) ? (int)sizeof(WideLds<MB>) : (int)sizeof(ShrinkLds);
 }
 
-template <int SPG, int MB>
+template <int SPG, int MB, bool A8>
 __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
 {
     __shared__ __align__(16) unsigned char smem[wide_lds_bytes<MB>()];
@@ -1727,7 +1904,7 @@ __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
     if (b < tables.shrink_blocks) {
         if (blockIdx.y != 0) return;
         const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
-        shrink_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
+        shrink_block<A8>(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     WideLds<MB> &lds = *reinterpret_cast<WideLds<MB> *>(smem);
@@ -1738,12 +1915,12 @@ __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
         const ProjArgs P = fetch_proj(a, pi);
         const int local = pb - first;
         const int groups = (tiles_n(P.N) + WIDE_TILES - 1) / WIDE_TILES;
-        wide_unit<SPG, MB>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
+        wide_unit<SPG, MB, A8>(a, P, pi, local % groups, 1 + local / groups, m0, lds);
     } else {
         const int mb_ = b - tables.shrink_blocks - tables.pre_base_blocks;
         const int pi = z * GROUP_PROJ + find_proj(tables.main, mb_, first);
         const ProjArgs P = fetch_proj(a, pi);
-        wide_unit<SPG, MB>(a, P, pi, mb_ - first, 0, m0, lds);
+        wide_unit<SPG, MB, A8>(a, P, pi, mb_ - first, 0, m0, lds);
     }
 }
 
@@ -1757,17 +1934,29 @@ static hipError_t launch_instance(const LayerArgs &a, const dim3 &grid, hipStrea
 // grid: x = the longest group's blocks, y = row chunks, z = groups of up to 16 projections
 hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s)
 {
-    const dim3 grid((unsigned)grid_x, (unsigned)(a.m_pad / rows_per_chunk(a.M)), (unsigned)groups);
+    const dim3 grid((unsigned)grid_x, (unsigned)(a.m_pad / rows_per_chunk(a.M_plan)), (unsigned)groups);
     if (a.wide) {
         // (the host puts only projections with the same group size into one such launch)
-        if (a.M <= 32) {
-            if (a.p[0].spg == 1)      wide_kernel<1, 2><<<grid, dim3(256), 0, s>>>(a);
-            else if (a.p[0].spg == 2) wide_kernel<2, 2><<<grid, dim3(256), 0, s>>>(a);
-            else                      wide_kernel<4, 2><<<grid, dim3(256), 0, s>>>(a);
+        const int spg = a.p[0].spg;
+        auto go = [&](auto kernel) { kernel<<<grid, dim3(256), 0, s>>>(a); };
+        if (a.a8) {
+            if (a.M_plan <= 32) {
+                if (spg == 1)      go(wide_kernel<1, 2, true>);
+                else if (spg == 2) go(wide_kernel<2, 2, true>);
+                else               go(wide_kernel<4, 2, true>);
+            } else {
+                if (spg == 1)      go(wide_kernel<1, 4, true>);
+                else if (spg == 2) go(wide_kernel<2, 4, true>);
+                else               go(wide_kernel<4, 4, true>);
+            }
+        } else if (a.M_plan <= 32) {
+            if (spg == 1)      go(wide_kernel<1, 2, false>);
+            else if (spg == 2) go(wide_kernel<2, 2, false>);
+            else               go(wide_kernel<4, 2, false>);
         } else {
-            if (a.p[0].spg == 1)      wide_kernel<1, 4><<<grid, dim3(256), 0, s>>>(a);
-            else if (a.p[0].spg == 2) wide_kernel<2, 4><<<grid, dim3(256), 0, s>>>(a);
-            else                      wide_kernel<4, 4><<<grid, dim3(256), 0, s>>>(a);
+            if (spg == 1)      go(wide_kernel<1, 4, false>);
+            else if (spg == 2) go(wide_kernel<2, 4, false>);
+            else               go(wide_kernel<4, 4, false>);
         }
         return hipGetLastError();
     }
