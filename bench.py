@@ -60,6 +60,8 @@ def parse_args():
                          "known traffic next to which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings "
                          "of the layer kernel can be scaled")
     ap.add_argument("--y-fp32", action="store_true")
+    ap.add_argument("--a8", action="store_true",
+                    help="int8 activations with one scale per tensor (mlora_w4a8_layer_step) instead of bf16")
     return ap.parse_args()
 
 
@@ -317,7 +319,7 @@ def main():
 
     rows0 = wl.make_rows(w.row_map, M, w.projs[0].n_adapters, w.cfg_id)
     U = len(set(int(a) for a in rows0 if a >= 0))
-    layer_bytes = sum(wl.algorithmic_bytes(p, M, U, ysz) for p in w.projs)
+    layer_bytes = sum(wl.algorithmic_bytes(p, M, U, ysz) - (M * p.K if args.a8 else 0) for p in w.projs)   # int8 rows: half the bytes of x
     layer_flops = sum(wl.algorithmic_flops(p, M) for p in w.projs)
     step_bytes, step_flops = layer_bytes * w.layers, layer_flops * w.layers
 
@@ -326,25 +328,44 @@ def main():
     t0 = time.time()
     sets = []                       # per copy: (projs, dxs, ys, ra) over all layers
     host_layer0 = None
+    host_scales0 = None
     for c in range(copies):
-        projs, dxs, ys = [], [], []
+        projs, dxs, ys, x_scales = [], [], [], []
         for layer in range(w.layers):
             probs, xs, rows = wl.make_layer(w, layer=c * w.layers + layer)
             projs += [device.upload_problem(p, dev) for p in probs]
             cache = {}
-            for x in xs:
-                if id(x) not in cache:
-                    cache[id(x)] = device.to_device(x, dev)
-                dxs.append(cache[id(x)])
+            if args.a8:
+                xs = list(xs)
+                for x in list(xs):
+                    if id(x) not in cache:
+                        xq, sc = wl.quantise_act_int8(wl.bf16_bits_to_f32(x))
+                        cache[id(x)] = (torch.from_numpy(xq).to(dev), xq, float(sc))
+                xs_q = [cache[id(x)][1] for x in xs]
+                x_scales += [cache[id(x)][2] for x in xs]
+                dxs += [cache[id(x)][0] for x in xs]
+                if c == 0 and layer == 0:
+                    host_scales0 = [cache[id(x)][2] for x in xs]
+                xs = xs_q
+            else:
+                for x in xs:
+                    if id(x) not in cache:
+                        cache[id(x)] = device.to_device(x, dev)
+                    dxs.append(cache[id(x)])
             ys += [device.alloc_y(M, p.shape.N, y_dtype, dev) for p in probs]
             if c == 0 and layer == 0:
                 host_layer0 = (probs, xs, rows)
         ra = torch.from_numpy(rows).to(dev)
-        sets.append((projs, dxs, ys, ra))
+        sets.append((projs, dxs, ys, ra, x_scales))
     # one workspace per copy, sized for the whole step: the calls of a step follow each other on
     # one stream, and a workspace serves calls of any geometry one after another
     plans, dep_plans, workspaces = [], [], []
-    for projs, dxs, ys, ra in sets:
+    for projs, dxs, ys, ra, x_scales in sets:
+        if args.a8:
+            ws = torch.zeros(max(lib.a8_workspace_bytes(projs, M), 256), dtype=torch.uint8, device=dev)
+            workspaces.append(ws)
+            plans.append([lib.LayerPlanA8(projs, dxs, x_scales, ys, ra, M, y_dtype, ws)])
+            continue
         ws = device.alloc_workspace(projs, M, dev)
         workspaces.append(ws)
         if args.per_layer_calls:
@@ -427,8 +448,12 @@ def main():
     msel = np.arange(M) if M <= 64 else np.unique(np.concatenate([[0, M - 1], np.arange(0, M, 37)]))
     for i in sample:
         p = probs0[i]
-        ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
-                            np.ascontiguousarray(xs0[i][msel]), np.ascontiguousarray(rows_h[msel]))
+        if args.a8:
+            ref = oracle.linear_a8(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
+                                   np.ascontiguousarray(xs0[i][msel]), host_scales0[i], np.ascontiguousarray(rows_h[msel]))
+        else:
+            ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
+                                np.ascontiguousarray(xs0[i][msel]), np.ascontiguousarray(rows_h[msel]))
         got = device.y_to_numpy(sets[0][2][i])[msel]
         max_rel_err = max(max_rel_err, float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))))
     assert max_rel_err <= (2e-4 if args.y_fp32 else 5e-3), max_rel_err
@@ -436,6 +461,8 @@ def main():
     # ---- the dominant (only) kernel; which one and how many launches a call makes is asked of
     # the library itself
     info = lib.layer_step_plan(plans[0][0].keep[0], M)
+    if args.a8:                                  # always blocks of four column tiles, one launch per 128 projections
+        info = dict(info, wide=True, launches=math.ceil(len(plans[0][0].keep[0]) / 128))
     launches_per_step = calls_per_step * info["launches"]
     n_ev = K * launches_per_step
     kern_s = ev_s / n_ev
@@ -443,9 +470,9 @@ def main():
     achieved = base_bytes / kern_s / 1e9
     wide = info["wide"]
     spg = w.projs[0].group // 32
-    kernel_name = ("wide_kernel<%d, %d>" % (spg, 2 if M <= 32 else 4)) if wide else \
+    kernel_name = ("wide_kernel<%d, %d, %s>" % (spg, 2 if M <= 32 else 4, "true" if args.a8 else "false")) if wide else \
         "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
-    kernel_tag = "wide_kernel" if wide else "layer_kernel"
+    kernel_tag = ("wide_kernel_a8" if args.a8 else "wide_kernel") if wide else "layer_kernel"
     achieved_tflops = (step_flops / launches_per_step) / kern_s / 1e12
     bound = BOUND.get(w.key, "hbm")
     traffic, traffic_src = measured_traffic(kernel_tag, w.key) if not args.per_layer_calls else (None, None)
@@ -461,14 +488,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "int8 x int4 -> int32, fp32 scales" if args.a8 else "bf16",
         "data": "synthetic",
         "config": {
             "workload": f"{w.key}: {w.description}",
             "projections": [f"{p.name} {p.K}x{p.N}" for p in w.projs],
             "M": M, "group": w.projs[0].group, "rank": w.projs[0].rank,
             "n_adapters": w.projs[0].n_adapters, "distinct_adapters": U, "layers": w.layers,
-            "y_dtype": "fp32" if args.y_fp32 else "bf16",
+            "y_dtype": "fp32" if args.y_fp32 else "bf16", "x_dtype": "int8, one scale per tensor" if args.a8 else "bf16",
             "rotating_copies": copies, "launch_mode": args.mode,
             "calls_per_step": calls_per_step,
         },
@@ -516,8 +543,11 @@ def main():
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 1000:
             t1 = time.perf_counter()
-            for p, x in zip(probs0, xs0):
-                oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows_h)
+            for i, (p, x) in enumerate(zip(probs0, xs0)):
+                if args.a8:
+                    oracle.linear_a8(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, host_scales0[i], rows_h)
+                else:
+                    oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows_h)
             t_cpu += time.perf_counter() - t1
             reps += 1
         result["cpu_baseline"] = {
@@ -529,7 +559,7 @@ def main():
                       f"{t_cpu:.1f} s of fp64 loops on {cores} threads",
             "us_per_linear": round(t_cpu / reps / len(probs0) * 1e6, 1),
         }
-        if w.key in ("c1", "c2", "c3"):
+        if w.key in ("c1", "c2", "c3") and not args.a8:
             # the small configurations also on ONE host thread (bounded the same way)
             oracle.set_threads(1)
             reps1, t1_cpu = 0, 0.0

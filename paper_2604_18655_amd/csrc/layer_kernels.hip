@@ -1407,7 +1407,7 @@ __device__ __forceinline__ void stream_loop_a8(f32x4 (&acc)[MB][4], const u32x4 
     using L = WideLds<MB>;
     using L8 = WideLdsA8<MB>;
     constexpr int S = L::XSTEPS;
-    constexpr int W = 8;
+    constexpr int W = MB == 4 ? 4 : 8;                     // k-steps of codes in registers
     constexpr int HALVES = W / S;
     const int last = n_ksteps - 1;
     u32x4 w[W];
