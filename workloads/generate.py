@@ -88,6 +88,31 @@ def make_x(M: int, K: int, cfg_id: int, layer: int, slot_index: int) -> np.ndarr
     return f32_to_bf16_bits(x)
 
 
+def fuse_gate_up(gate: Problem, up: Problem) -> Problem:
+    """The gate and up projections of an MLP as ONE projection in the layout the fused SwiGLU
+    output stage expects: every tile of 64 output rows of the weight holds 32 gate rows followed
+    by the up rows of the same features (rows are quantised one by one, so codes and scales are
+    just re-ordered), and the two LoRA pairs become one of twice the rank:
+    A = [A_gate; A_up], B = [[B_gate, 0], [0, B_up]] re-ordered like the weight rows."""
+    g, u = gate.shape, up.shape
+    assert (g.K, g.N, g.group, g.rank, g.n_adapters, g.alpha) == (u.K, u.N, u.group, u.rank, u.n_adapters, u.alpha)
+    assert g.N % 32 == 0
+    F, r, n_ad = g.N, g.rank, g.n_adapters
+    order = np.empty(2 * F, np.int64)                      # fused row -> row of concat(gate, up)
+    for t in range(F // 32):
+        order[64 * t:64 * t + 32] = np.arange(32 * t, 32 * t + 32)
+        order[64 * t + 32:64 * t + 64] = F + np.arange(32 * t, 32 * t + 32)
+    wq = np.concatenate([gate.wq, up.wq], axis=0)[order]
+    scales = np.concatenate([gate.scales, up.scales], axis=0)[order]
+    lora_a = np.concatenate([gate.lora_a, up.lora_a], axis=1)              # [n_ad][2r][K]
+    b = np.zeros((n_ad, 2 * F, 2 * r), np.uint16)
+    b[:, :F, :r] = gate.lora_b
+    b[:, F:, r:] = up.lora_b
+    shape = ProjShape("gate_up", g.K, 2 * F, g.group, 2 * r, n_ad, g.alpha)
+    return Problem(shape, np.ascontiguousarray(wq), np.ascontiguousarray(scales), np.ascontiguousarray(lora_a),
+                   np.ascontiguousarray(b[:, order, :]))
+
+
 def quantise_act_int8(x: np.ndarray) -> Tuple[np.ndarray, np.float32]:
     """Per-tensor symmetric int8 quantisation of activations (Section 3.3 of the paper): one
     scale max|x| / 127 in float32 (1 for an all-zero tensor), round to nearest even, clamp."""
