@@ -147,6 +147,47 @@ mlora_status mlora_w4_workspace_status(const void *workspace, int32_t *status_wo
  * Process-wide, read when a call is enqueued.  Returns the previous value. */
 int32_t mlora_w4_debug_spin_limit(int32_t limit);
 
+/* The layer step with the decoder layer's glue folded into the output stage (Section 3.3: graph
+ * optimisations -- constant folding and operator fusion; Table 10's scalar folding).  As
+ * mlora_w4_layer_step, for at most 16 projections, each with an epilogue applied to its outputs
+ * before they are stored, in this order:
+ *   1. v = row_scale[m] * (base product + LoRA term)       row_scale fp32 [M], NULL = 1.
+ *      This is RMSNorm in front of the projection with its weight folded away: with W' = W diag(g)
+ *      and A' = A diag(g) prepared offline, W (g * x / rms(x)) = (1 / rms(x)) W' x, so the call
+ *      takes the un-normalised rows as x and mlora_rms_scale's output as row_scale.
+ *   2. a pair operation on columns (c, c + 32) of every tile of 64 output columns (N % 64 == 0):
+ *      MLORA_PAIR_ROPE    rotary position encoding for heads of 64 features laid out as tiles:
+ *                         v[c]    <- v[c] cos[m][c % 32] - v[c + 32] sin[m][c % 32]
+ *                         v[c+32] <- v[c + 32] cos[m][c % 32] + v[c] sin[m][c % 32]
+ *                         rope_cos, rope_sin fp32 [M][32]: the angle of row m's position times
+ *                         the i-th frequency, prepared by the caller;
+ *      MLORA_PAIR_SWIGLU  the output has N / 2 columns: y[m][32 t + i] = silu(v[64 t + i]) *
+ *                         v[64 t + 32 + i], silu(z) = z / (1 + exp(-z)).  The projection is the
+ *                         gate and up projections of the MLP stored as one weight whose tile t
+ *                         holds gate columns 32 t .. 32 t + 31 followed by the up columns of the
+ *                         same features (an offline rearrangement of the two weights; their LoRA
+ *                         pairs become one of twice the rank).
+ *   3. + residual[m][n]                                     bf16 [M][N_out], NULL = none
+ * then rounding to y_dtype.  ys[i] is [M][N_out], N_out = N (N / 2 for MLORA_PAIR_SWIGLU).
+ * Errors as mlora_w4_layer_step, plus MLORA_ESHAPE for more than 16 projections or a pair
+ * operation with N % 64 != 0, MLORA_EINVAL for an unknown pair operation or missing tables. */
+enum { MLORA_PAIR_NONE = 0, MLORA_PAIR_ROPE = 1, MLORA_PAIR_SWIGLU = 2 };
+typedef struct mlora_w4_epilogue {
+    const float *row_scale;
+    int32_t pair_op;
+    const float *rope_cos;
+    const float *rope_sin;
+    const void *residual;
+} mlora_w4_epilogue;
+mlora_status mlora_w4_layer_step_fused(const mlora_w4_proj *projs, const mlora_w4_epilogue *epis, int32_t n_proj,
+                                       const void *const *xs, void *const *ys,
+                                       const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* scale[m] = 1 / sqrt(mean_k x[m][k]^2 + eps) for bf16 rows x [M][K] (K % 8 == 0): the per-row
+ * factor of RMSNorm, computed in fp32 in a fixed order.  x 16-byte aligned, scale fp32 [M]. */
+mlora_status mlora_rms_scale(const void *x, int32_t M, int32_t K, float eps, float *scale, void *stream);
+
 /* The layer step with int8 activations (Section 3.3: activations quantised to int8 with one
  * scale per tensor, weights to int4).  As mlora_w4_layer_step, except that
  *   xs[i]        int8 [M][K]: the quantised rows; the activation they stand for is

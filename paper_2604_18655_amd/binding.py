@@ -19,6 +19,7 @@ exported_symbols = (
     "mlora_w4_layer_step_static", "mlora_w4_layer_step_plan",
     "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
     "mlora_w4a8_workspace_bytes", "mlora_w4a8_layer_step",
+    "mlora_w4_layer_step_fused", "mlora_rms_scale",
     "mlora_ds2d_rows", "mlora_ds2d_layout", "mlora_ds2d_workspace_bytes", "mlora_ds2d_step",
 )
 
@@ -39,6 +40,11 @@ class _Ds2dStruct(C.Structure):
     _fields_ = [("n_streams", C.c_int32), ("n_forecast", C.c_int32), ("depth", C.c_int32),
                 ("branch", C.c_int32 * 8), ("next_depth", C.c_int32), ("next_branch", C.c_int32 * 8),
                 ("vocab", C.c_int32), ("logits_dtype", C.c_int32)]
+
+
+class _EpilogueStruct(C.Structure):
+    _fields_ = [("row_scale", C.c_void_p), ("pair_op", C.c_int32), ("rope_cos", C.c_void_p),
+                ("rope_sin", C.c_void_p), ("residual", C.c_void_p)]
 
 
 class _TreeAttnStruct(C.Structure):
@@ -97,6 +103,11 @@ def load_library():
         lib.mlora_w4a8_layer_step.restype = C.c_int
         lib.mlora_w4a8_layer_step.argtypes = [pp, i32, C.POINTER(vp), C.POINTER(C.c_float), C.POINTER(vp), vp,
                                               i32, i32, vp, sz, vp]
+        lib.mlora_w4_layer_step_fused.restype = C.c_int
+        lib.mlora_w4_layer_step_fused.argtypes = [pp, C.POINTER(_EpilogueStruct), i32, C.POINTER(vp), C.POINTER(vp),
+                                                  vp, i32, i32, vp, sz, vp]
+        lib.mlora_rms_scale.restype = C.c_int
+        lib.mlora_rms_scale.argtypes = [vp, i32, i32, C.c_float, vp, vp]
         dp = C.POINTER(_Ds2dStruct)
         ip = C.POINTER(i32)
         lib.mlora_ds2d_rows.restype = C.c_int
@@ -244,6 +255,47 @@ class LayerPlan:
                      self.ws, self.ws_bytes, _stream() if stream is None else stream)
         if st != 0:
             raise MloraError(st, "mlora_w4_layer_step")
+
+
+PAIR_NONE, PAIR_ROPE, PAIR_SWIGLU = 0, 1, 2
+
+
+class Epilogue:
+    """What a fused call does to one projection's outputs (mlora_w4_epilogue); keeps its tensors."""
+
+    def __init__(self, row_scale=None, pair_op: int = PAIR_NONE, rope_cos=None, rope_sin=None, residual=None):
+        self.keep = (row_scale, rope_cos, rope_sin, residual)
+        self.struct = _EpilogueStruct(_ptr(row_scale), pair_op, _ptr(rope_cos), _ptr(rope_sin), _ptr(residual))
+
+
+class LayerPlanFused:
+    """Marshalled arguments of mlora_w4_layer_step_fused."""
+
+    def __init__(self, projs: Sequence[Proj], epis: Sequence[Epilogue], xs: Sequence, ys: Sequence, row_adapter,
+                 M: int, y_dtype: int, workspace):
+        assert len(projs) == len(xs) == len(ys) == len(epis)
+        self.keep = (list(projs), list(epis), list(xs), list(ys), row_adapter, workspace)
+        self.n = len(projs)
+        self.arr = _proj_array(projs)
+        self.epis = (_EpilogueStruct * self.n)(*[e.struct for e in epis])
+        self.xs = (C.c_void_p * self.n)(*[_ptr(x) for x in xs])
+        self.ys = (C.c_void_p * self.n)(*[_ptr(y) for y in ys])
+        self.rows = _ptr(row_adapter)
+        self.M, self.y_dtype = int(M), int(y_dtype)
+        self.ws = _ptr(workspace)
+        self.ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self.fn = load_library().mlora_w4_layer_step_fused
+
+    def run(self, stream: Optional[int] = None) -> None:
+        st = self.fn(self.arr, self.epis, self.n, self.xs, self.ys, self.rows, self.M, self.y_dtype,
+                     self.ws, self.ws_bytes, _stream() if stream is None else stream)
+        if st != 0:
+            raise MloraError(st, "mlora_w4_layer_step_fused")
+
+
+def rms_scale(x, M: int, K: int, eps: float, scale, stream: Optional[int] = None) -> None:
+    _check(load_library().mlora_rms_scale(_ptr(x), M, K, float(eps), _ptr(scale),
+                                          _stream() if stream is None else stream), "mlora_rms_scale")
 
 
 def a8_workspace_bytes(projs: Sequence[Proj], M: int) -> int:

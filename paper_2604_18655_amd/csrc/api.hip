@@ -436,7 +436,8 @@ static mlora_status check_call(const mlora_w4_proj *projs, int32_t n_proj, const
 static mlora_status enqueue_call(const mlora_w4_proj *projs, int32_t n_proj, const void *const *xs,
                                  void *const *ys, const int32_t *row_adapter, int32_t M, int32_t y_dtype,
                                  bool lora_on, char *workspace, size_t workspace_bytes, size_t data_total,
-                                 hipStream_t s, const float *x_scales = nullptr)
+                                 hipStream_t s, const float *x_scales = nullptr,
+                                 const mlora_w4_epilogue *epis = nullptr)
 {
     const bool a8 = x_scales != nullptr;
     const int Mp = plan_rows(M, a8);
@@ -452,6 +453,17 @@ static mlora_status enqueue_call(const mlora_w4_proj *projs, int32_t n_proj, con
         a->M = M;
         a->M_plan = Mp;
         a->a8 = a8;
+        a->fused = epis != nullptr;
+        if (epis) {
+            for (int i = 0; i < count && i < GROUP_PROJ; ++i) {
+                const mlora_w4_epilogue &e = epis[first + i];
+                a->epi[i].row_scale = e.row_scale;
+                a->epi[i].rope_cos = e.rope_cos;
+                a->epi[i].rope_sin = e.rope_sin;
+                a->epi[i].residual = reinterpret_cast<const uint16_t *>(e.residual);
+                a->epi[i].pair_op = e.pair_op;
+            }
+        }
         a->y_fp32 = (y_dtype == MLORA_Y_FP32);
         a->m_pad = m_pad_of(Mp);
         a->spin_limit = g_spin_limit;
@@ -518,6 +530,51 @@ mlora_status mlora_w4_layer_step_static(const mlora_w4_proj *projs, int32_t n_pr
     for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
     return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
                         ws, STATIC_SCRATCH_BYTES, data_total, (hipStream_t)stream);
+}
+
+mlora_status mlora_w4_layer_step_fused(const mlora_w4_proj *projs, const mlora_w4_epilogue *epis, int32_t n_proj,
+                                       const void *const *xs, void *const *ys,
+                                       const int32_t *row_adapter, int32_t M, int32_t y_dtype,
+                                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    mlora_status st = check_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype);
+    if (st != MLORA_OK) return st;
+    if (!epis) return MLORA_EINVAL;
+    if (n_proj > GROUP_PROJ) return MLORA_ESHAPE;
+    for (int i = 0; i < n_proj; ++i) {
+        const mlora_w4_epilogue &e = epis[i];
+        if (e.pair_op != MLORA_PAIR_NONE && e.pair_op != MLORA_PAIR_ROPE && e.pair_op != MLORA_PAIR_SWIGLU) return MLORA_EINVAL;
+        if (e.pair_op != MLORA_PAIR_NONE && projs[i].N % TILE_N != 0) return MLORA_ESHAPE;
+        if (e.pair_op == MLORA_PAIR_ROPE && (!e.rope_cos || !e.rope_sin)) return MLORA_EINVAL;
+        if ((e.row_scale && (reinterpret_cast<uintptr_t>(e.row_scale) & 3u)) ||
+            (e.rope_cos && (reinterpret_cast<uintptr_t>(e.rope_cos) & 3u)) ||
+            (e.rope_sin && (reinterpret_cast<uintptr_t>(e.rope_sin) & 3u)) ||
+            (e.residual && (reinterpret_cast<uintptr_t>(e.residual) & 1u))) return MLORA_EALIGN;
+    }
+    if (M == 0) return MLORA_OK;
+    size_t ctrl_total, data_total;
+    st = plan_call(projs, n_proj, M, true, ctrl_total, data_total);
+    if (st != MLORA_OK) return st;
+    const size_t need = workspace_need(ctrl_total, data_total);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return MLORA_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MLORA_EALIGN;
+    }
+    bool any_lora = false;
+    for (int i = 0; i < n_proj; ++i) any_lora = any_lora || projs[i].n_adapters > 0;
+    return enqueue_call(projs, n_proj, xs, ys, row_adapter, M, y_dtype, any_lora && row_adapter != nullptr,
+                        need > 0 ? reinterpret_cast<char *>(workspace) : nullptr, workspace_bytes, data_total,
+                        (hipStream_t)stream, nullptr, epis);
+}
+
+mlora_status mlora_rms_scale(const void *x, int32_t M, int32_t K, float eps, float *scale, void *stream)
+{
+    if (M < 0 || M > MLORA_MAX_ROWS || K <= 0 || K % 8 != 0 || K > (1 << 24)) return MLORA_ESHAPE;
+    if (M == 0) return MLORA_OK;
+    if (!x || !scale || !(eps >= 0.0f)) return MLORA_EINVAL;
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(scale) & 3u)) return MLORA_EALIGN;
+    return launch_rms_scale(reinterpret_cast<const uint16_t *>(x), M, K, eps, scale, (hipStream_t)stream) == hipSuccess
+               ? MLORA_OK : MLORA_EHIP;
 }
 
 size_t mlora_w4a8_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int32_t M)

@@ -106,6 +106,23 @@ __host__ __device__ inline int shrink_ctr(int p, int r) { return (p * CTR_REPL +
 constexpr size_t WS_HEADER_BYTES = 256;        // status word at the front of every workspace
 constexpr int SPIN_LIMIT_DEFAULT = 200000;     // x ~0.5 us: far beyond any launch, still finite
 
+// What a fused call does to the outputs of a projection before they are stored (all optional):
+//   v = row_scale[m] * (base + LoRA term); a pair operation on columns (c, c + 32) of every
+//   64-column tile; + residual[m][n].
+// Pair operations: PAIR_ROPE rotates (v[c], v[c+32]) by the angle whose cosine and sine are
+// rope_cos/sin[m][c % 32] (heads of 64 features: a tile is a head); PAIR_SWIGLU stores
+// silu(v[c]) * v[c+32] at column 32 * tile + c % 32 of an output of N / 2 columns (the weight
+// holds 32 gate columns and the 32 up columns of the same features in every tile).
+enum { PAIR_NONE = 0, PAIR_ROPE = 1, PAIR_SWIGLU = 2 };
+struct EpiArgs {
+    const float *row_scale;        // fp32 [M]
+    const float *rope_cos;         // fp32 [M][32]
+    const float *rope_sin;
+    const uint16_t *residual;      // bf16 [M][N_out]
+    int pair_op;
+    int pad_;
+};
+
 struct LayerArgs {
     // Slice z of the grid holds, in this order, the shrink blocks, the split-K blocks (units 1..)
     // and the finishing blocks (unit 0) of the projections of group z; first block of each
@@ -124,6 +141,8 @@ struct LayerArgs {
                                // blocks): M, except that calls with int8 activations always run
                                // wide blocks and are laid out as for at least 17 rows
     int a8;                    // x is int8 with one scale per tensor (ProjArgs::x_scale)
+    int fused;                 // outputs go through epi[] (one group of at most 16 projections)
+    EpiArgs epi[GROUP_PROJ];
     int y_fp32;
     int m_pad;                 // M rounded up to whole row chunks of the base kernel
     int spin_limit;            // polls a block makes before it gives up waiting (0: gives up at once)
@@ -198,6 +217,7 @@ hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int 
                              int *seg_adapter, int *seg_start, int *n_seg, hipStream_t s);
 hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s);
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
+hipError_t launch_rms_scale(const uint16_t *x, int M, int K, float eps, float *scale, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
 // Two families of base blocks.  "Tile" blocks cover one column tile and their four waves split

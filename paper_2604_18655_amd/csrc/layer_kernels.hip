@@ -411,6 +411,56 @@ struct EpiPrefetch {
     }
 };
 
+// Outputs of a fused call: the four values a lane holds of one row, columns 16 * j + l16 of a
+// tile (so (v[0], v[2]) and (v[1], v[3]) are the pairs 32 columns apart), go through the
+// projection's EpiArgs and are stored one by one.
+__device__ __forceinline__ void store_fused(const LayerArgs &a, const ProjArgs &P, int pi, int m, int tile, int l16,
+                                            float (&v)[4])
+{
+    if (m >= a.M) return;
+    const EpiArgs &E = a.epi[pi];
+    if (E.row_scale) {
+        const float rs = E.row_scale[m];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] *= rs;
+    }
+    const int N = P.N;
+    if (E.pair_op == PAIR_SWIGLU) {
+        const int n_out = N >> 1;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int n = tile * (TILE_N / 2) + 16 * jj + l16;
+            if (n >= n_out) continue;
+            const float g = v[jj];
+            float o = g / (1.0f + expf(-g)) * v[jj + 2];
+            const size_t at = (size_t)m * n_out + n;
+            if (E.residual) o += bf16_bits_to_float(E.residual[at]);
+            if (a.y_fp32) reinterpret_cast<float *>(P.y)[at] = o;
+            else reinterpret_cast<uint16_t *>(P.y)[at] = float_to_bf16_bits(o);
+        }
+        return;
+    }
+    if (E.pair_op == PAIR_ROPE) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const float c = E.rope_cos[(size_t)m * 32 + 16 * jj + l16], sn = E.rope_sin[(size_t)m * 32 + 16 * jj + l16];
+            const float x0 = v[jj], x1 = v[jj + 2];
+            v[jj] = x0 * c - x1 * sn;
+            v[jj + 2] = x1 * c + x0 * sn;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n = tile * TILE_N + 16 * j + l16;
+        if (n >= N) continue;
+        const size_t at = (size_t)m * N + n;
+        float o = v[j];
+        if (E.residual) o += bf16_bits_to_float(E.residual[at]);
+        if (a.y_fp32) reinterpret_cast<float *>(P.y)[at] = o;
+        else reinterpret_cast<uint16_t *>(P.y)[at] = float_to_bf16_bits(o);
+    }
+}
+
 constexpr int FAST_RANK = 16;                  // the epilogue prefetch covers ranks up to this
 
 // LDS of a base block: the per-wave staging buffers, the per-wave partial tiles (red) and
@@ -761,7 +811,10 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                 const int m = m0 + elem_ml(4 * mb);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = poisoned ? nan_f : v[j];
-                if (m < M) {
+                if (a.fused) {
+                    float vv[4] = {v[0], v[1], v[2], v[3]};
+                    store_fused(a, P, pi, m, tile, l16, vv);
+                } else if (m < M) {
                     if (a.y_fp32) {
                         float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;
 #pragma unroll
@@ -807,6 +860,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         }
         __syncthreads();
 
+        float fv[EPT];                                     // a fused call's outputs, stored after the loop
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq) fv[qq] = 0.f;
 #pragma unroll
         for (int qq = 0; qq < EPT; ++qq) {
             const int off = red_at(qq >> 2, wave, lane) + (qq & 3);
@@ -842,8 +898,16 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     v += l;
                 }
                 v = poisoned ? nan_f : v;
-                if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
+                if (a.fused) fv[qq] = v;
+                else if (a.y_fp32) reinterpret_cast<float *>(P.y)[(size_t)m * N + n] = v;
                 else reinterpret_cast<uint16_t *>(P.y)[(size_t)m * N + n] = float_to_bf16_bits(v);
+            }
+        }
+        if (a.fused && ku == 0) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                float vv[4] = {fv[4 * mb], fv[4 * mb + 1], fv[4 * mb + 2], fv[4 * mb + 3]};
+                store_fused(a, P, pi, m0 + elem_ml(4 * mb), tile, l16, vv);
             }
         }
     }
@@ -1816,7 +1880,15 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{1.f, 1.f, 1.f, 1.f} * __uint_as_float(0x7FC00000u);
     }
-    if (tile_ok && ku == 0) {
+    if (tile_ok && ku == 0 && a.fused) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float vv[4] = {acc[mb][0][e], acc[mb][1][e], acc[mb][2][e], acc[mb][3][e]};
+                store_fused(a, P, pi, m0 + 16 * mb + 4 * lq + e, tile, l16, vv);
+            }
+    } else if (tile_ok && ku == 0) {
         const bool full = tile * TILE_N + TILE_N <= N;
         if (full) {
             // rows of 64 outputs through a wave-private LDS buffer, so that a lane stores 16
