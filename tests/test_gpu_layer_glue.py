@@ -157,3 +157,89 @@ def test_fused_call_argument_checks(gpu):
     with pytest.raises(lib.MloraError):              # more than 16 projections
         ys = [device.alloc_y(4, 200, 0) for _ in range(17)]
         lib.LayerPlanFused([proj] * 17, [lib.Epilogue()] * 17, [x] * 17, ys, None, 4, 0, ws).run()
+
+
+def build_layer(gpu, seed, S, parent, is_forecast, Hq, Hkv, F, Lp, cap, n_ad=3, rank=8):
+    """A decoder layer of hidden = 64 * Hq on the device plus every host tensor it was made from."""
+    lib, device, torch = gpu
+    from paper_2604_18655_amd.decoder import DecoderLayerStep
+    D, H, KV = 64, 64 * Hq, 64 * Hkv
+    R = len(parent)
+    M = S * R
+    mk = lambda name, K, N, i: wl.make_problem(wl.ProjShape(name, K, N, 32, rank, n_ad, 2.0), seed, 0, i)
+    host = {"q": mk("q", H, H, 0), "k": mk("k", H, KV, 1), "v": mk("v", H, KV, 2), "o": mk("o", H, H, 3),
+            "gate_up": wl.fuse_gate_up(mk("gate", H, F, 4), mk("up", H, F, 5)), "down": mk("down", F, H, 6)}
+    dev = {k: device.upload_problem(p) for k, p in host.items()}
+    inp = wl.make_attention_inputs(seed, S, parent, is_forecast, Hq, Hkv, D, Lp, 0, cap)
+    dd = lambda a: device.to_device(a) if a.size else None
+    k_new = torch.zeros((M, Hkv * D), dtype=torch.int16, device="cuda")
+    v_new = torch.zeros((M, Hkv * D), dtype=torch.int16, device="cuda")
+    att = lib.TreeAttention(Hq, Hkv, D, S, R, inp.scale, dd(inp.k_prefill), dd(inp.v_prefill), None, None,
+                            dd(inp.k_stream), dd(inp.v_stream), torch.from_numpy(inp.len_stream).cuda(), k_new, v_new,
+                            torch.from_numpy(inp.parent).cuda(), torch.from_numpy(inp.is_forecast).cuda(), Lp, 0, cap)
+    rng = np.random.default_rng(seed)
+    h = wl.make_x(M, H, seed, 0, 9)
+    ang = glue.rope_angles(rng.integers(0, 3000, M))
+    cos, sin = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+    rows = rng.integers(-1, n_ad, M).astype(np.int32)
+    layer = DecoderLayerStep(dev["q"], dev["k"], dev["v"], dev["o"], dev["gate_up"], dev["down"], att,
+                             device.to_device(h), dev_f32(torch, cos), dev_f32(torch, sin),
+                             torch.from_numpy(rows).cuda(), M)
+    return layer, host, inp, h, cos, sin, rows
+
+
+def bits_of(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("S,branch", [(2, (3, 2)), (8, None)])
+def test_decoder_layer_every_stage_and_end_to_end(gpu, S, branch):
+    """A whole decoder layer through the library (7 calls), every stage compared with the oracle
+    fed with the very tensors the stage read on the device, and the final rows with the oracle's
+    own chain (intermediates rounded to bf16 where the device stores bf16)."""
+    lib, device, torch = gpu
+    if branch is None:
+        parent, fc = np.asarray([-1, 0, 0, 1], np.int32), np.zeros(4, np.uint8)
+    else:
+        parent, fc = wl.ds2d_tree(branch)
+    Hq, Hkv, F = 4, 2, 512
+    layer, host, inp, h, cos, sin, rows = build_layer(gpu, 3100 + S, S, parent, fc, Hq, Hkv, F, 96, 24)
+    layer.run()
+    torch.cuda.synchronize()
+    assert lib.workspace_status(layer.ws) == 0
+    M = S * len(parent)
+    f64 = lambda bits: bf16_bits_to_f32(bits).astype(np.float64)
+    lin = lambda key, x_bits, **kw: glue.fused_linear(host[key].wq, host[key].scales, 32, host[key].lora_a,
+                                                      host[key].lora_b, 2.0, x_bits, rows, **kw)
+    att = lambda q, k, v: oracle.tree_attention(q.reshape(M, Hq, 64), inp.k_prefill, inp.v_prefill, inp.k_fprefix,
+                                                inp.v_fprefix, inp.k_stream, inp.v_stream, inp.len_stream,
+                                                k.reshape(M, Hkv, 64), v.reshape(M, Hkv, 64), inp.parent,
+                                                inp.is_forecast, S, inp.scale).reshape(M, Hq * 64)
+    s1 = layer.s1.cpu().numpy()
+    assert np.max(np.abs(s1 / glue.rms_scale(f64(h), 1e-5) - 1)) <= 1e-5
+    q, k, v = bits_of(layer.q), bits_of(layer.k_new), bits_of(layer.v_new)
+    rope = dict(row_scale=s1, pair_op="rope", cos=cos, sin=sin)
+    assert rel_err(f64(q), lin("q", h, **rope)) <= TOL
+    assert rel_err(f64(k), lin("k", h, **rope)) <= TOL
+    assert rel_err(f64(v), lin("v", h, row_scale=s1)) <= TOL
+    attn = bits_of(layer.attn)
+    assert rel_err(f64(attn), att(q, k, v)) <= TOL
+    h2 = bits_of(layer.h2)
+    assert rel_err(f64(h2), lin("o", attn, residual_bits=h)) <= TOL
+    s2 = layer.s2.cpu().numpy()
+    assert np.max(np.abs(s2 / glue.rms_scale(f64(h2), 1e-5) - 1)) <= 1e-5
+    act = bits_of(layer.act)
+    assert rel_err(f64(act), lin("gate_up", h2, row_scale=s2, pair_op="swiglu")) <= TOL
+    out = bits_of(layer.out)
+    assert rel_err(f64(out), lin("down", act, residual_bits=h2)) <= TOL
+
+    # the oracle's own chain, end to end
+    rb = lambda y: f32_to_bf16_bits(y.astype(np.float32))
+    o_s1 = glue.rms_scale(f64(h), 1e-5)
+    o_rope = dict(row_scale=o_s1, pair_op="rope", cos=cos, sin=sin)
+    o_q, o_k, o_v = rb(lin("q", h, **o_rope)), rb(lin("k", h, **o_rope)), rb(lin("v", h, row_scale=o_s1))
+    o_attn = rb(att(o_q, o_k, o_v))
+    o_h2 = rb(lin("o", o_attn, residual_bits=h))
+    o_act = rb(lin("gate_up", o_h2, row_scale=glue.rms_scale(f64(o_h2), 1e-5), pair_op="swiglu"))
+    o_out = lin("down", o_act, residual_bits=o_h2)
+    assert rel_err(f64(out), o_out) <= 2e-2
