@@ -45,7 +45,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4_decode",
-                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down, c4_attention, c4_ds2d")
+                    help="c4_decode (default), c1, c2, c3, c4_prefill, c5_up, c5_down, c4_attention, c4_ds2d, c4_layer")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K steps are captured once in a HIP graph and replayed; "
                          "eager: one library call per step from Python")
@@ -175,6 +175,143 @@ def bench_ds2d(args):
     print(json.dumps(result))
 
 
+def bench_layer(args):
+    """--workload c4_layer: ONE decoder layer of the 1B-like model with its true dependencies, at the
+    rows of the c4 decoding step (8 streams x 4 tree rows): rms scale, fused q/k/v (+ rotary
+    encoding), masked tree attention, o (+ residual), rms scale, fused gate/up (+ SwiGLU), down
+    (+ residual): 7 library calls, 8 launches per step."""
+    import numpy as np
+    import torch
+
+    import oracle
+    import paper_2604_18655_amd as lib
+    import workloads as wl
+    from oracle import layer_glue as glue
+    from paper_2604_18655_amd import device
+    from paper_2604_18655_amd.decoder import DecoderLayerStep
+    from workloads.generate import bf16_bits_to_f32, f32_to_bf16_bits
+
+    lib.load_library()
+    torch.cuda.set_device(0)
+    S, R, Hq, Hkv, D, H, KV, F, Lp, cap = 8, 4, 32, 8, 64, 2048, 512, 8192, 2048, 128
+    M, n_ad, rank = S * R, 8, 16
+    parent, fc = np.asarray([-1, 0, 0, 1], np.int32), np.zeros(4, np.uint8)
+    shapes = wl.llama1b_layer_shapes()
+    rows = wl.make_rows("block:4", M, n_ad, 4)
+    U = len(set(int(a) for a in rows if a >= 0))
+    lin_bytes = sum(wl.algorithmic_bytes(p, M, U, 2) for p in shapes)
+    copies = args.copies or 16
+    t0 = time.time()
+    layers, host0 = [], None
+    att_bytes = 0
+    for c in range(copies):
+        mk = lambda i: wl.make_problem(shapes[i], 40, c, i)
+        host = {"q": mk(0), "k": mk(1), "v": mk(2), "o": mk(3), "gate_up": wl.fuse_gate_up(mk(4), mk(5)), "down": mk(6)}
+        dev = {k: device.upload_problem(p) for k, p in host.items()}
+        inp = wl.make_attention_inputs(5000 + c, S, parent, fc, Hq, Hkv, D, Lp, 0, cap)
+        dd = lambda a: device.to_device(a) if a.size else None
+        k_new = torch.zeros((M, KV), dtype=torch.int16, device="cuda")
+        v_new = torch.zeros((M, KV), dtype=torch.int16, device="cuda")
+        att = lib.TreeAttention(Hq, Hkv, D, S, R, inp.scale, dd(inp.k_prefill), dd(inp.v_prefill), None, None,
+                                dd(inp.k_stream), dd(inp.v_stream), torch.from_numpy(inp.len_stream).cuda(),
+                                k_new, v_new, torch.from_numpy(inp.parent).cuda(),
+                                torch.from_numpy(inp.is_forecast).cuda(), Lp, 0, cap)
+        h = wl.make_x(M, H, 40, c, 9)
+        ang = glue.rope_angles(np.random.default_rng(c).integers(0, 3000, M))
+        cos, sin = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+        layer = DecoderLayerStep(dev["q"], dev["k"], dev["v"], dev["o"], dev["gate_up"], dev["down"], att,
+                                 device.to_device(h), torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda(),
+                                 torch.from_numpy(rows).cuda(), M)
+        layers.append(layer)
+        if c == 0:
+            host0 = (host, inp, h, cos, sin)
+            att_bytes = 2 * 2 * Hkv * D * (Lp + int(inp.len_stream.sum())) + 2 * 2 * M * Hkv * D + 2 * 2 * M * Hq * D
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    step_bytes = lin_bytes + att_bytes
+
+    def run_step(i, stream=None):
+        layers[i % copies].run(stream)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(K):
+                run_step(args.warmup + i, side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev0.record()
+    graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    step_s = ev0.elapsed_time(ev1) * 1e-3 / K
+    for layer in layers:
+        assert lib.workspace_status(layer.ws) == 0
+
+    # copy 0 against the oracle's own chain (intermediates rounded to bf16 where the device stores bf16)
+    host, inp, h, cos, sin = host0
+    f64 = lambda bits: bf16_bits_to_f32(bits).astype(np.float64)
+    rb = lambda y: f32_to_bf16_bits(y.astype(np.float32))
+    lin = lambda key, x_bits, **kw: glue.fused_linear(host[key].wq, host[key].scales, 32, host[key].lora_a,
+                                                      host[key].lora_b, 2.0, x_bits, rows, **kw)
+    att_o = lambda q, k, v: oracle.tree_attention(q.reshape(M, Hq, D), inp.k_prefill, inp.v_prefill, inp.k_fprefix,
+                                                  inp.v_fprefix, inp.k_stream, inp.v_stream, inp.len_stream,
+                                                  k.reshape(M, Hkv, D), v.reshape(M, Hkv, D), inp.parent,
+                                                  inp.is_forecast, S, inp.scale).reshape(M, Hq * D)
+
+    def oracle_layer():
+        s1 = glue.rms_scale(f64(h), 1e-5)
+        rope = dict(row_scale=s1, pair_op="rope", cos=cos, sin=sin)
+        q, k, v = rb(lin("q", h, **rope)), rb(lin("k", h, **rope)), rb(lin("v", h, row_scale=s1))
+        h2 = rb(lin("o", rb(att_o(q, k, v)), residual_bits=h))
+        act = rb(lin("gate_up", h2, row_scale=glue.rms_scale(f64(h2), 1e-5), pair_op="swiglu"))
+        return lin("down", act, residual_bits=h2)
+
+    t1 = time.perf_counter()
+    ref = oracle_layer()
+    t_cpu = time.perf_counter() - t1
+    got = f64(layers[0].out.cpu().numpy().view(np.uint16))
+    max_rel_err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    assert max_rel_err <= 2e-2, max_rel_err
+    gbs = step_bytes / (elapsed / K) / 1e9
+    result = {
+        "metric": "µs per decoder layer step (7 multi-LoRA W4 linears + tree attention + glue) + achieved HBM GB/s, 1 MI355X",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / K, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_layer: one decoder layer of the 1B-like model in dependency order, 8 streams x 4 tree rows",
+                   "M": M, "hidden": H, "kv_width": KV, "ffn": F, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D,
+                   "len_prefill": Lp, "cap_stream": cap, "group": 32, "rank": rank, "n_adapters": n_ad,
+                   "distinct_adapters": U, "calls_per_step": 7, "launches_per_step": 8,
+                   "rotating_copies": copies, "launch_mode": "graph"},
+        "us_per_step": round(elapsed * 1e6 / K, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "algorithmic_bytes_per_step": int(step_bytes), "max_rel_err": float(f"{max_rel_err:.3e}"),
+        "setup_s": round(setup_s, 1),
+        "roofline": {"kernel": "layer_kernel<2, 32> x 4 + tree_attn_partial/combine + rms_scale_kernel x 2 (one step)",
+                     "bound": "hbm", "achieved": round(step_bytes / step_s / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(step_bytes / step_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(step_bytes), "avg_launch_us": round(step_s * 1e6, 3),
+                     "launches_timed": K,
+                     "timed_with": "two HIP events around the timed region on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = {"value": round(step_bytes / t_cpu / 1e9, 4), "unit": "GB/s",
+                                  "cores": oracle.max_threads(), "kind": "oracle",
+                                  "sample": f"one whole layer of the same workload, {t_cpu:.1f} s",
+                                  "us_per_step": round(t_cpu * 1e6, 1)}
+    print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
 def bench_attention(args):
     """--workload c4_attention: the masked tree attention of the 16-layer stack's decoding step
     (8 streams x 4 tree rows, 32 query heads on 8 kv heads of 64 features, 2048 prefill
@@ -296,6 +433,9 @@ def main():
     if args.workload == "c4_ds2d":
         bench_ds2d(args)
         return
+    if args.workload == "c4_layer":
+        bench_layer(args)
+        return
     if args.workload == "c4_attention":
         bench_attention(args)
         return
@@ -366,7 +506,15 @@ def main():
             workspaces.append(ws)
             plans.append([lib.LayerPlanA8(projs, dxs, x_scales, ys, ra, M, y_dtype, ws)])
             continue
-        ws = device.alloc_workspace(projs, M, dev)
+        # (sized for the largest of the calls that will use it: the whole step, and each of the
+        # dependency-order calls, whose smaller launches may be cut differently)
+        names = [p.name for p in w.projs]
+        dep_ok = n_proj == 7 and all(any(n in grp for grp in DEPENDENCY_ORDER) for n in names)
+        need = lib.workspace_bytes(projs, M)
+        if dep_ok:
+            for grp in DEPENDENCY_ORDER:
+                need = max(need, lib.workspace_bytes([projs[names.index(n)] for n in grp], M))
+        ws = torch.zeros(max(need, 256), dtype=torch.uint8, device=dev)
         workspaces.append(ws)
         if args.per_layer_calls:
             plans.append([lib.LayerPlan(projs[l * n_proj:(l + 1) * n_proj], dxs[l * n_proj:(l + 1) * n_proj],
@@ -374,8 +522,7 @@ def main():
                           for l in range(w.layers)])
         else:
             plans.append([lib.LayerPlan(projs, dxs, ys, ra, M, y_dtype, ws)])
-        names = [p.name for p in w.projs]
-        if n_proj == 7 and all(any(n in grp for grp in DEPENDENCY_ORDER) for n in names):
+        if dep_ok:
             calls = []
             for l in range(w.layers):
                 for grp in DEPENDENCY_ORDER:
