@@ -672,6 +672,19 @@ def main():
         },
     }
 
+    # per-step times of a short eager loop (one HIP event pair per step): spread, next to the mean above
+    n_each = min(50, K)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
+    for i, (e0, e1) in enumerate(pairs):
+        e0.record()
+        run_step(args.warmup + i, None, plans)
+        e1.record()
+    torch.cuda.synchronize()
+    each = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in pairs)
+    result["eager_per_step_us"] = {"n": n_each, "min": round(each[0], 3), "median": round(each[n_each // 2], 3),
+                                   "max": round(each[-1], 3),
+                                   "what": "one event pair per step, launched from Python one by one"}
+
     if dep_plans and not args.no_dependency_order:
         Kd = max(1, K // 4)
         el_d, _ = timed(dep_plans, Kd, min(args.warmup, 5))
