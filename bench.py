@@ -618,7 +618,7 @@ def main():
     wide = info["wide"]
     spg = w.projs[0].group // 32
     kernel_name = ("wide_kernel<%d, %d, %s>" % (spg, 2 if M <= 32 else 4, "true" if args.a8 else "false")) if wide else \
-        "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if M <= 16 else "2, 24" if M <= 24 else "2, 32")
+        "layer_kernel<%s>" % ("1, 8" if M <= 8 else "1, 16" if info["rows_per_chunk"] == 16 else "2, 24" if M <= 24 else "2, 32")
     kernel_tag = ("wide_kernel_a8" if args.a8 else "wide_kernel") if wide else "layer_kernel"
     achieved_tflops = (step_flops / launches_per_step) / kern_s / 1e12
     bound = BOUND.get(w.key, "hbm")

@@ -2032,8 +2032,11 @@ hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t 
         }
         return hipGetLastError();
     }
-    if (a.M <= 8)  return launch_instance<1, 8>(a, grid, s);
-    if (a.M <= 16) return launch_instance<1, 16>(a, grid, s);
+    // (M_plan, not M: a short launch of 17 to 32 rows is laid out as chunks of 16 rows, and the
+    // kernel has to be the one the host laid the grid, the shrink blocks and the counters out for)
+    const int rows = rows_per_chunk(a.M_plan);
+    if (a.m_pad % rows != 0 || (int)grid.y * rows < a.M) return hipErrorInvalidValue;
+    if (rows == 16) return a.M <= 8 ? launch_instance<1, 8>(a, grid, s) : launch_instance<1, 16>(a, grid, s);
     if (a.M <= 24) return launch_instance<2, 24>(a, grid, s);
     return launch_instance<2, 32>(a, grid, s);
 }

@@ -105,7 +105,9 @@ def test_layer_step_plan_names_the_kernel_family():
 
     one = (binding._ProjStruct * 1)(proj(K=2048, N=2048, rank=16))
     assert plan(one, 1, 8)[:3] == [1, 0, 16]
-    assert plan(one, 1, 32)[:3] == [1, 0, 32]          # 8 blocks of four tiles: far below 300
+    assert plan(one, 1, 32)[:3] == [1, 0, 16]          # a short launch: two chunks of 16 rows
+    seven = (binding._ProjStruct * 7)(*[proj(K=2048, N=n, rank=16) for n in (2048, 512, 512, 2048, 8192, 8192, 2048)])
+    assert plan(seven, 7, 32)[:3] == [1, 0, 32]         # a whole layer: one chunk of 32 rows
     assert plan(one, 1, 33)[:3] == [1, 1, 64]
     many = (binding._ProjStruct * 130)(*[proj(K=2048, N=2048, rank=16) for _ in range(130)])
     got = plan(many, 130, 32)                           # 128 + 2 projections: two launches
