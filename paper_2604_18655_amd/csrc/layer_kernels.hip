@@ -848,14 +848,39 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         if (fast) {
             t_entries_to_lds();
         } else if (lora) {
-            for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
-                const int ml = idx / P.r16, jj = idx % P.r16;
-                const int ad = a.row_adapter[m0 + ml];
-                float v = 0.f;
-                if (ad >= 0 && ad < P.n_adapters)
-                    for (int kc = 0; kc < P.kch; ++kc)
-                        v += load_shared(P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj);
-                lds.t_row(ml)[jj] = v * P.alpha;
+            // four entries of t per thread and four K chunks at a time: 16 loads in flight instead of
+            // one after another (a rank of 32 at 32 rows is four entries per thread, each the sum
+            // of up to 16 partials)
+            for (int i0 = 0; i0 < rows_here * P.r16; i0 += 4 * NT) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                bool live[4];
+                const float *src[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = i0 + q * NT + tid;
+                    const int ml = min(idx / P.r16, rows_here - 1), jj = idx % P.r16;
+                    const int ad = a.row_adapter[m0 + ml];
+                    live[q] = idx < rows_here * P.r16 && ad >= 0 && ad < P.n_adapters;
+                    src[q] = live[q] ? P.t_part + (size_t)(m0 + ml) * P.r16 + jj : P.t_part;
+                }
+                for (int kc0 = 0; kc0 < P.kch; kc0 += 4) {
+                    float pv[4][4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            pv[q][c] = load_shared(src[q] + (live[q] ? (size_t)min(kc0 + c, P.kch - 1) * M * P.r16 : 0));
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (kc0 + c < P.kch) v[q] += pv[q][c];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = i0 + q * NT + tid;
+                    if (idx < rows_here * P.r16) lds.t_row(idx / P.r16)[idx % P.r16] = live[q] ? v[q] * P.alpha : 0.f;
+                }
             }
         }
         __syncthreads();
@@ -863,6 +888,36 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         float fv[EPT];                                     // a fused call's outputs, stored after the loop
 #pragma unroll
         for (int qq = 0; qq < EPT; ++qq) fv[qq] = 0.f;
+        // ranks above 16: B[a(m)][n] . t[m] of this thread's outputs, the rows of B fetched 32 ranks
+        // of four outputs at a time (16 loads in flight), summed in rank order
+        float ll[EPT];
+#pragma unroll
+        for (int qq = 0; qq < EPT; ++qq) ll[qq] = 0.f;
+        if (lora && !fast && ku == 0) {
+            for (int jj0 = 0; jj0 < P.rank; jj0 += 32) {
+#pragma unroll
+                for (int h = 0; h < EPT; h += 4) {
+                    uint4 bq[4][4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int ad = elem_ad(h + q);
+                        const int n = min(tile * TILE_N + elem_col(h + q), N - 1);
+                        const uint16_t *brow = P.lora_b + ((size_t)max(ad, 0) * N + n) * P.rank;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            bq[q][c] = *reinterpret_cast<const uint4 *>(brow + min(jj0 + 8 * c, P.rank - 8));
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const bool mine = elem_ad(h + q) >= 0;
+                        const float *tr = lds.t_row(elem_ml(h + q));
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (mine && jj0 + 8 * c < P.rank) ll[h + q] = dot8(bq[q][c], tr + jj0 + 8 * c, ll[h + q]);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int qq = 0; qq < EPT; ++qq) {
             const int off = red_at(qq >> 2, wave, lane) + (qq & 3);
@@ -891,9 +946,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                             if (P.rank > 8) l = dot8(pf.b[qq][1], lds.t_row(ml) + 8, l);
                         }
                     } else {
-                        const uint16_t *brow = P.lora_b + ((size_t)ad * N + n) * P.rank;
-                        for (int jj = 0; jj < P.rank; jj += 8)
-                            l = dot8(*reinterpret_cast<const uint4 *>(brow + jj), lds.t_row(ml) + jj, l);
+                        l = ll[qq];
                     }
                     v += l;
                 }
