@@ -381,17 +381,18 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[4], StreamRegs &ra, Str
 // Loads the epilogue needs that do not depend on other blocks, requested ahead of their use (all
 // unconditional; a thread with nothing to fetch re-reads a valid address).  The N outputs of a
 // thread lie in one row, 16 columns apart, so their rows of B differ by a fixed stride.
-template <int N, int MBR>
+template <int N, int MBR, int FR>
 struct EpiPrefetch {
+    static constexpr int H = FR / 16;        // entries of t per thread and row block
     const uint16_t *bad[MBR];                // B of each row's adapter (or a safe address)
     int brank[MBR];                          // rank (0 with the safe address: every offset is 0)
     int n0, nlast;                           // column of output 0; last valid column
-    // entries of t this thread sums: row t_ml + 16 * i, rank index t_jj
-    const float *tp[MBR];                    // the entry in t_part[0] (or a safe address)
-    size_t tstride[MBR];                     // distance between K chunks of t_part (0 with the safe address)
+    // entries of t this thread sums: row t_ml + 16 * i, rank indices t_jj + 16 * h
+    const float *tp[MBR][H];                 // the entry in t_part[0] (or a safe address)
+    size_t tstride[MBR][H];                  // distance between K chunks of t_part (0 with the safe address)
     int kch, t_ml, t_jj;
-    bool t_mine[MBR];
-    uint4 b[N > 0 ? N : 1][2];
+    bool t_mine[MBR][H];
+    uint4 b[N > 0 ? N : 1][FR / 8];
     __device__ __forceinline__ void issue()
     {
         // (global, not generic, loads: a generic load also counts as an LDS access, and every
@@ -403,10 +404,10 @@ struct EpiPrefetch {
             // the address passes through an empty asm: without it the compiler hoists these loads
             // to the top of the kernel and then spills their results across the whole K loop
             if ((q & 3) == 0) asm volatile("" : "+v"(bad[mb]));
-            const int second = brank[mb] > 8 ? 8 : 0;
             const uint16_t *row = bad[mb] + (unsigned)(min(n0 + 16 * (q & 3), nlast) * brank[mb]);
-            b[q][0] = __builtin_bit_cast(uint4, *(G *)(row));
-            b[q][1] = __builtin_bit_cast(uint4, *(G *)(row + second));
+#pragma unroll
+            for (int c = 0; c < FR / 8; ++c)     // (pieces past the rank re-read the first one)
+                b[q][c] = __builtin_bit_cast(uint4, *(G *)(row + (brank[mb] > 8 * c ? 8 * c : 0)));
         }
     }
 };
@@ -461,7 +462,9 @@ __device__ __forceinline__ void store_fused(const LayerArgs &a, const ProjArgs &
     }
 }
 
-constexpr int FAST_RANK = 16;                  // the epilogue prefetch covers ranks up to this
+// the epilogue prefetch covers ranks up to this: 16 in the kernels for up to 16 rows (their register
+// budget), 32 where a chunk has 32 rows (the prefetch there starts once the K loop's registers are free)
+template <int MB> constexpr int fast_rank() { return MB == 1 ? 16 : 32; }
 
 // LDS of a base block: the per-wave staging buffers, the per-wave partial tiles (red) and
 // alpha * t of the chunk's rows.  Decode shapes: a wave's partial tile lies over its OWN staging
@@ -538,8 +541,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const bool lora = (ku == 0) && (a.row_adapter != nullptr) && (P.n_adapters > 0);
     const int rows_here = min(ROWS, M - m0);
     constexpr bool PREFETCH = EPT <= 8;                    // more outputs per thread: too many registers
-    // (ranks up to FAST_RANK: r16 == 16, and the chunk's entries of t number at most MB per thread)
-    const bool fast = PREFETCH && lora && P.rank <= FAST_RANK;
+    // (ranks up to FR: the entries of t of a chunk number at most MB * FR / 16 per thread)
+    constexpr int FR = fast_rank<MB>();
+    const bool fast = PREFETCH && lora && P.rank <= FR;
     // element qq of this thread: tile row and column (cheap to recompute, so not kept live)
     static_assert(WAVES == 4, "one wave per element of an MFMA result register");
     auto elem_ml = [&](int qq) { return (qq >> 2) * 16 + 4 * lq + wave; };
@@ -559,8 +563,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         for (int j = 0; j < 4; ++j) acc[mb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // epilogue operands fetched while the last round is being computed: the rows of B of this
-    // thread's outputs (ranks up to FAST_RANK) and one entry of t per thread
-    EpiPrefetch<PREFETCH ? EPT : 0, MB> pf;
+    // thread's outputs (ranks up to FR) and its entries of t
+    EpiPrefetch<PREFETCH ? EPT : 0, MB, FR> pf;
+    constexpr int TH = FR / 16;
     auto prefetch_setup = [&]() {
         pf.t_ml = tid >> 4;
         pf.t_jj = tid & 15;
@@ -573,46 +578,48 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
             const bool ok = fast && ad >= 0;
             pf.bad[i] = ok ? P.lora_b + (size_t)ad * N * P.rank : reinterpret_cast<const uint16_t *>(P.codes);
             pf.brank[i] = ok ? P.rank : 0;
-            pf.t_mine[i] = fast && pf.t_ml + 16 * i < rows_here;
-            pf.tp[i] = pf.t_mine[i] ? P.t_part + (size_t)(m0 + pf.t_ml + 16 * i) * P.r16 + pf.t_jj
-                                    : reinterpret_cast<const float *>(P.codes);
-            pf.tstride[i] = pf.t_mine[i] ? (size_t)M * P.r16 : 0;
+#pragma unroll
+            for (int h = 0; h < TH; ++h) {
+                pf.t_mine[i][h] = fast && pf.t_ml + 16 * i < rows_here && pf.t_jj + 16 * h < P.r16;
+                pf.tp[i][h] = pf.t_mine[i][h] ? P.t_part + (size_t)(m0 + pf.t_ml + 16 * i) * P.r16 + pf.t_jj + 16 * h
+                                              : reinterpret_cast<const float *>(P.codes);
+                pf.tstride[i][h] = pf.t_mine[i][h] ? (size_t)M * P.r16 : 0;
+            }
         }
     };
     // alpha * t of this thread's entries -> LDS: the K-chunk partials of the shrink step, all
     // requested at once and summed in fixed order
     auto t_entries_to_lds = [&]() {
-        float ts[MB];
+        constexpr int E = MB * TH;                         // entries of this thread: (row block i, half h) = e / TH, e % TH
+        float ts[E];
         if (pf.kch <= 4) {
-            float tv[MB][4];
+            float tv[E][4];
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
+            for (int e = 0; e < E; ++e)
 #pragma unroll
                 for (int kc = 0; kc < 4; ++kc)
-                    tv[i][kc] = load_shared(pf.tp[i] + (size_t)min(kc, pf.kch - 1) * pf.tstride[i]);
+                    tv[e][kc] = load_shared(pf.tp[e / TH][e % TH] + (size_t)min(kc, pf.kch - 1) * pf.tstride[e / TH][e % TH]);
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                ts[i] = 0.f;
+            for (int e = 0; e < E; ++e) {
+                ts[e] = 0.f;
 #pragma unroll
-                for (int kc = 0; kc < 4; ++kc) ts[i] += kc < pf.kch ? tv[i][kc] : 0.f;
+                for (int kc = 0; kc < 4; ++kc) ts[e] += kc < pf.kch ? tv[e][kc] : 0.f;
             }
         } else {
-            float tv[MB][MAX_KCHUNKS];
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
+            for (int e = 0; e < E; ++e) {
+                float tv[MAX_KCHUNKS];
 #pragma unroll
                 for (int kc = 0; kc < MAX_KCHUNKS; ++kc)
-                    tv[i][kc] = load_shared(pf.tp[i] + (size_t)min(kc, pf.kch - 1) * pf.tstride[i]);
+                    tv[kc] = load_shared(pf.tp[e / TH][e % TH] + (size_t)min(kc, pf.kch - 1) * pf.tstride[e / TH][e % TH]);
+                ts[e] = 0.f;
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                ts[i] = 0.f;
-#pragma unroll
-                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) ts[i] += kc < pf.kch ? tv[i][kc] : 0.f;
+                for (int kc = 0; kc < MAX_KCHUNKS; ++kc) ts[e] += kc < pf.kch ? tv[kc] : 0.f;
             }
         }
 #pragma unroll
-        for (int i = 0; i < MB; ++i)
-            if (pf.t_mine[i]) lds.t_row(pf.t_ml + 16 * i)[pf.t_jj] = ts[i] * P.alpha;
+        for (int e = 0; e < E; ++e)
+            if (pf.t_mine[e / TH][e % TH]) lds.t_row(pf.t_ml + 16 * (e / TH))[pf.t_jj + 16 * (e % TH)] = ts[e] * P.alpha;
     };
 
     // the two constants of expand_codes arrive as kernel arguments so that they live in
@@ -792,19 +799,21 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                         for (int u = 0; u < PU; ++u) v[j] += u + 1 < P.ksplit ? pv[4 * mb + j][u] : 0.f;
                 }
                 if (lora) {
-                    float t[FAST_RANK];
+                    // (entries of a row of t past the rank are not written and not used)
+                    float t[FR];
                     const f32x4 *tr = reinterpret_cast<const f32x4 *>(lds.t_row(elem_ml(4 * mb)));
 #pragma unroll
-                    for (int i = 0; i < FAST_RANK / 4; ++i) {
+                    for (int i = 0; i < FR / 4; ++i) {
                         const f32x4 tq = tr[i];
                         t[4 * i] = tq[0]; t[4 * i + 1] = tq[1]; t[4 * i + 2] = tq[2]; t[4 * i + 3] = tq[3];
                     }
                     const bool mine = elem_ad(4 * mb) >= 0;
-                    const bool two = P.rank > 8;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         float l = dot8(pf.b[4 * mb + j][0], t, 0.f);
-                        if (two) l = dot8(pf.b[4 * mb + j][1], t + 8, l);
+#pragma unroll
+                        for (int c = 1; c < FR / 8; ++c)
+                            if (P.rank > 8 * c) l = dot8(pf.b[4 * mb + j][c], t + 8 * c, l);
                         v[j] += mine ? l : 0.f;
                     }
                 }
@@ -943,7 +952,9 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                     if (fast) {
                         if constexpr (PREFETCH) {
                             l = dot8(pf.b[qq][0], lds.t_row(ml), l);
-                            if (P.rank > 8) l = dot8(pf.b[qq][1], lds.t_row(ml) + 8, l);
+#pragma unroll
+                            for (int c = 1; c < FR / 8; ++c)
+                                if (P.rank > 8 * c) l = dot8(pf.b[qq][c], lds.t_row(ml) + 8 * c, l);
                         }
                     } else {
                         l = ll[qq];
