@@ -1292,6 +1292,29 @@ __device__ __forceinline__ int find_proj(const i32x16 &begin, int b, int &first)
 }
 
 // blocks per compute unit the registers are budgeted for (LDS allows as many for these shapes)
+// Block index -> (block of the group, row chunk).  The row chunks of one block of columns stream
+// the same weights.  Workgroups go to the chip's 8 XCDs in turn (index mod 8), and every XCD has
+// an L2 of its own, so the grid is laid out in runs of 8 blocks x all chunks with the chunk
+// varying in steps of 8: index = (b / 8) * 8 * chunks + chunk * 8 + b % 8.  All chunks of a block
+// then run on one XCD at about the same time, and its weights come from HBM once and from that
+// L2 for the other chunks.  (Chunk-major order, a whole pass over the weights between two chunks,
+// read 5.9 x the algorithmic bytes from HBM at 512 rows.)  A producer still has a smaller index
+// than its consumer: shrink blocks work at chunk 0 only, and a split-K block and the block that
+// finishes its tile have the same chunk.
+__device__ __forceinline__ void split_block_index(const LayerArgs &a, int rows, int &b, int &chunk)
+{
+    const unsigned id = blockIdx.x;
+    const unsigned chunks = (unsigned)(a.m_pad / rows);
+    if (chunks == 1) {
+        b = (int)id;
+        chunk = 0;
+    } else {
+        const unsigned run = id / (8u * chunks), r = id - run * 8u * chunks;
+        chunk = (int)(r >> 3);
+        b = (int)(run * 8u + (r & 7u));
+    }
+}
+
 template <int MB, int XR> constexpr int occupancy_of() { return MB == 1 && XR == 8 ? 3 : 2; }
 
 template <int MB, int XR>
@@ -1300,11 +1323,12 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     __shared__ __align__(16) unsigned char smem[pre_lds_bytes<MB, XR>()];
     const int z = (int)blockIdx.z;
     const LaunchTables tables = pin_launch_args(a, z);
-    const int b = (int)blockIdx.x;
+    int b, chunk;
+    split_block_index(a, 16 * MB, b, chunk);
     if (b >= tables.group_blocks) return;                  // (the slices are as long as the longest group)
     int first;
     if (b < tables.shrink_blocks) {
-        if (blockIdx.y != 0) return;
+        if (chunk != 0) return;
         const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
         // (the instances with one block of 16 rows are the ones launched for M <= 16)
         if constexpr (MB == 1) shrink_row_block(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkRowLds *>(smem));
@@ -1312,7 +1336,7 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
         return;
     }
     const BaseLdsOf<MB, XR> lds{smem};
-    const int m0 = (int)blockIdx.y * 16 * MB;
+    const int m0 = chunk * 16 * MB;
     // (one call site for both kinds of base block: the kernel's code is large, and what runs
     // once per launch is paid for by instruction fetch)
     const bool pre = b < tables.shrink_blocks + tables.pre_base_blocks;
@@ -2034,17 +2058,18 @@ __global__ __launch_bounds__(256, 2) void wide_kernel(const LayerArgs a)
     __shared__ __align__(16) unsigned char smem[wide_lds_bytes<MB>()];
     const int z = (int)blockIdx.z;
     const LaunchTables tables = pin_launch_args(a, z);
-    const int b = (int)blockIdx.x;
+    int b, chunk;
+    split_block_index(a, 16 * MB, b, chunk);
     if (b >= tables.group_blocks) return;
     int first;
     if (b < tables.shrink_blocks) {
-        if (blockIdx.y != 0) return;
+        if (chunk != 0) return;
         const int pi = z * GROUP_PROJ + find_proj(tables.shrink, b, first);
         shrink_block<A8>(a, fetch_proj(a, pi), pi, b - first, *reinterpret_cast<ShrinkLds *>(smem));
         return;
     }
     WideLds<MB> &lds = *reinterpret_cast<WideLds<MB> *>(smem);
-    const int m0 = (int)blockIdx.y * 16 * MB;
+    const int m0 = chunk * 16 * MB;
     if (b < tables.shrink_blocks + tables.pre_base_blocks) {
         const int pb = b - tables.shrink_blocks;
         const int pi = z * GROUP_PROJ + find_proj(tables.pre, pb, first);
@@ -2067,10 +2092,14 @@ static hipError_t launch_instance(const LayerArgs &a, const dim3 &grid, hipStrea
     return hipGetLastError();
 }
 
-// grid: x = the longest group's blocks, y = row chunks, z = groups of up to 16 projections
+// grid: x = the longest group's blocks x row chunks (see split_block_index), z = groups of up to 16 projections
 hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s)
 {
-    const dim3 grid((unsigned)grid_x, (unsigned)(a.m_pad / rows_per_chunk(a.M_plan)), (unsigned)groups);
+    const int n_chunks = a.m_pad / rows_per_chunk(a.M_plan);
+    // (several chunks: runs of 8 blocks, see split_block_index; blocks past a group's last one exit at once)
+    const long long gx = n_chunks == 1 ? grid_x : (long long)((grid_x + 7) / 8 * 8) * n_chunks;
+    if (gx > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)gx, 1u, (unsigned)groups);
     if (a.wide) {
         // (the host puts only projections with the same group size into one such launch)
         const int spg = a.p[0].spg;
@@ -2099,7 +2128,7 @@ hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t 
     // (M_plan, not M: a short launch of 17 to 32 rows is laid out as chunks of 16 rows, and the
     // kernel has to be the one the host laid the grid, the shrink blocks and the counters out for)
     const int rows = rows_per_chunk(a.M_plan);
-    if (a.m_pad % rows != 0 || (int)grid.y * rows < a.M) return hipErrorInvalidValue;
+    if (a.m_pad % rows != 0 || n_chunks * rows < a.M) return hipErrorInvalidValue;
     if (rows == 16) return a.M <= 8 ? launch_instance<1, 8>(a, grid, s) : launch_instance<1, 16>(a, grid, s);
     if (a.M <= 24) return launch_instance<2, 24>(a, grid, s);
     return launch_instance<2, 32>(a, grid, s);
