@@ -152,6 +152,22 @@ def test_wide_blocks_at_17_to_32_rows(gpu, K, N, G, r, n_ad, M):
     check_linear(gpu, prob, x, rows, f"wide32 K{K} N{N} G{G} r{r} a{n_ad} M{M}")
 
 
+@pytest.mark.parametrize("K,N,G,r,n_ad,M", [
+    (1024, 700, 32, 16, 5, 200),      # 4 chunks of 64 rows (the last with 8), 3 blocks of columns: a run of 8 is not full
+    (2560, 2100, 64, 16, 9, 330),     # 6 chunks, 9 blocks of columns, several K units: runs of 8 plus a remainder
+    (512, 130, 128, 8, 3, 1000),      # 16 chunks, one block of columns
+])
+def test_many_row_chunks(gpu, K, N, G, r, n_ad, M):
+    """Calls with several row chunks lay their blocks out in runs of 8 with the chunk varying in
+    steps of 8 (all chunks of a block of columns on one XCD): every (block, chunk) pair must be
+    computed exactly once whatever the counts are."""
+    prob = random_problem(K + N + M, K, N, G, r, n_ad)
+    rng = np.random.default_rng(M)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    rows = rng.integers(-1, n_ad, size=M).astype(np.int32)
+    check_linear(gpu, prob, x, rows, f"chunks K{K} N{N} G{G} r{r} a{n_ad} M{M}")
+
+
 def test_wide_extreme_and_zero_scales(gpu):
     """The wide kernel keeps its accumulators in units of the current group's scale: scales that
     jump by many orders of magnitude between groups, and zero scales, must not disturb it."""
