@@ -856,6 +856,18 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         // t[m] = alpha * sum of the shrink step's K-chunk partials (fixed order)
         if (fast) {
             t_entries_to_lds();
+        } else if (lora && MB == 1) {
+            // (the kernels for up to 16 rows keep this path short: it is rare there, and its size
+            // costs the common path instruction fetches)
+            for (int idx = tid; idx < rows_here * P.r16; idx += NT) {
+                const int ml = idx / P.r16, jj = idx % P.r16;
+                const int ad = a.row_adapter[m0 + ml];
+                float v = 0.f;
+                if (ad >= 0 && ad < P.n_adapters)
+                    for (int kc = 0; kc < P.kch; ++kc)
+                        v += load_shared(P.t_part + ((size_t)kc * M + (m0 + ml)) * P.r16 + jj);
+                lds.t_row(ml)[jj] = v * P.alpha;
+            }
         } else if (lora) {
             // four entries of t per thread and four K chunks at a time: 16 loads in flight instead of
             // one after another (a rank of 32 at 32 rows is four entries per thread, each the sum
@@ -902,7 +914,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
         float ll[EPT];
 #pragma unroll
         for (int qq = 0; qq < EPT; ++qq) ll[qq] = 0.f;
-        if (lora && !fast && ku == 0) {
+        if (MB == 2 && lora && !fast && ku == 0) {
             for (int jj0 = 0; jj0 < P.rank; jj0 += 32) {
 #pragma unroll
                 for (int h = 0; h < EPT; h += 4) {
@@ -956,8 +968,12 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                             for (int c = 1; c < FR / 8; ++c)
                                 if (P.rank > 8 * c) l = dot8(pf.b[qq][c], lds.t_row(ml) + 8 * c, l);
                         }
-                    } else {
+                    } else if (MB == 2) {
                         l = ll[qq];
+                    } else {
+                        const uint16_t *brow = P.lora_b + ((size_t)ad * N + n) * P.rank;
+                        for (int jj = 0; jj < P.rank; jj += 8)
+                            l = dot8(*reinterpret_cast<const uint4 *>(brow + jj), lds.t_row(ml) + jj, l);
                     }
                     v += l;
                 }
