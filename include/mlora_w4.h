@@ -128,8 +128,10 @@ size_t mlora_w4_workspace_bytes(const mlora_w4_proj *projs, int32_t n_proj, int3
  * nothing is launched.  info (HOST memory, 5 int32): [0] kernel launches of the call (one per
  * 128 projections; from 17 rows on also a new one where the group size changes),
  * [1] 1 if the first launch runs blocks of four column tiles ("wide_kernel"), 0 if blocks of
- * one column tile ("layer_kernel"), [2] rows per row chunk (16, 32 or 64), [3] and [4] the
- * first launch's grid: blocks along x, groups of 16 projections along z.
+ * one column tile ("layer_kernel"), [2] rows per row chunk (16, 32 or 64; a short launch of 17
+ * to 32 rows runs as two chunks of 16), [3] and [4] the first launch's grid: blocks per row chunk
+ * (grid.x is that times the number of chunks, rounded up to runs of 8 when there are several)
+ * and groups of 16 projections along z.
  * MLORA_EINVAL for null pointers or n_proj <= 0, MLORA_ESHAPE for shapes the library refuses. */
 mlora_status mlora_w4_layer_step_plan(const mlora_w4_proj *projs, int32_t n_proj, int32_t M, int32_t *info);
 
