@@ -171,8 +171,14 @@ int32_t mlora_w4_debug_spin_limit(int32_t limit);
  *                         pairs become one of twice the rank).
  *   3. + residual[m][n]                                     bf16 [M][N_out], NULL = none
  * then rounding to y_dtype.  ys[i] is [M][N_out], N_out = N (N / 2 for MLORA_PAIR_SWIGLU).
+ * RMSNorm between two projections without a kernel of its own: with sq_out (fp32
+ * [M][ceil(N / 64)]) a projection also leaves, per row and column tile, the sum of the squares
+ * of the outputs it stored (as rounded to y_dtype); the projection that takes those outputs as
+ * its x names that array as sq_in with sq_parts = ceil(N_producer / 64) and sq_eps, instead of
+ * row_scale, and scales by 1 / sqrt(sum over parts / K + sq_eps).  Sums run in a fixed order.
  * Errors as mlora_w4_layer_step, plus MLORA_ESHAPE for more than 16 projections or a pair
- * operation with N % 64 != 0, MLORA_EINVAL for an unknown pair operation or missing tables. */
+ * operation with N % 64 != 0, MLORA_EINVAL for an unknown pair operation, missing tables, or
+ * sq_in together with row_scale. */
 enum { MLORA_PAIR_NONE = 0, MLORA_PAIR_ROPE = 1, MLORA_PAIR_SWIGLU = 2 };
 typedef struct mlora_w4_epilogue {
     const float *row_scale;
@@ -180,6 +186,10 @@ typedef struct mlora_w4_epilogue {
     const float *rope_cos;
     const float *rope_sin;
     const void *residual;
+    const float *sq_in;          /* NULL, or partial sums of squares of the rows of x (not with row_scale) */
+    int32_t sq_parts;
+    float sq_eps;
+    float *sq_out;               /* NULL, or where to leave this projection's own partial sums */
 } mlora_w4_epilogue;
 mlora_status mlora_w4_layer_step_fused(const mlora_w4_proj *projs, const mlora_w4_epilogue *epis, int32_t n_proj,
                                        const void *const *xs, void *const *ys,

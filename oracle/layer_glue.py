@@ -67,10 +67,30 @@ def swiglu_pairs(v: np.ndarray) -> np.ndarray:
     return out
 
 
+def scale_from_parts(sq_parts: np.ndarray, K: int, eps: float) -> np.ndarray:
+    """Row scale of RMSNorm from partial sums of squares of a row (any partition of its K entries)."""
+    return 1.0 / np.sqrt(np.sum(np.asarray(sq_parts, np.float64), axis=1) / K + eps)
+
+
+def tile_squares(y: np.ndarray, tile_cols: int = 64) -> np.ndarray:
+    """[M][ceil(N / tile_cols)]: sum of squares of every run of tile_cols columns of y."""
+    y = np.asarray(y, np.float64)
+    M, N = y.shape
+    tiles = -(-N // tile_cols)
+    out = np.zeros((M, tiles), np.float64)
+    for t in range(tiles):
+        out[:, t] = np.sum(y[:, t * tile_cols:(t + 1) * tile_cols] ** 2, axis=1)
+    return out
+
+
 def fused_linear(wq, scales, group, lora_a, lora_b, alpha, x_bits, row_adapter, row_scale=None,
-                 pair_op: str = "none", cos=None, sin=None, residual_bits=None) -> np.ndarray:
-    """The linear layer (oracle.c) followed by: row scale, pair operation, residual."""
+                 pair_op: str = "none", cos=None, sin=None, residual_bits=None, sq_in=None, sq_eps: float = 0.0) -> np.ndarray:
+    """The linear layer (oracle.c) followed by: row scale (given, or made from the partial sums
+    of squares sq_in of the rows of x), pair operation, residual."""
     y = _linear(wq, scales, group, lora_a, lora_b, alpha, x_bits, row_adapter)
+    if sq_in is not None:
+        assert row_scale is None
+        row_scale = scale_from_parts(sq_in, np.asarray(x_bits).shape[1], sq_eps)
     if row_scale is not None:
         y = y * np.asarray(row_scale, np.float64)[:, None]
     if pair_op == "rope":

@@ -44,7 +44,8 @@ class _Ds2dStruct(C.Structure):
 
 class _EpilogueStruct(C.Structure):
     _fields_ = [("row_scale", C.c_void_p), ("pair_op", C.c_int32), ("rope_cos", C.c_void_p),
-                ("rope_sin", C.c_void_p), ("residual", C.c_void_p)]
+                ("rope_sin", C.c_void_p), ("residual", C.c_void_p), ("sq_in", C.c_void_p),
+                ("sq_parts", C.c_int32), ("sq_eps", C.c_float), ("sq_out", C.c_void_p)]
 
 
 class _TreeAttnStruct(C.Structure):
@@ -263,9 +264,11 @@ PAIR_NONE, PAIR_ROPE, PAIR_SWIGLU = 0, 1, 2
 class Epilogue:
     """What a fused call does to one projection's outputs (mlora_w4_epilogue); keeps its tensors."""
 
-    def __init__(self, row_scale=None, pair_op: int = PAIR_NONE, rope_cos=None, rope_sin=None, residual=None):
-        self.keep = (row_scale, rope_cos, rope_sin, residual)
-        self.struct = _EpilogueStruct(_ptr(row_scale), pair_op, _ptr(rope_cos), _ptr(rope_sin), _ptr(residual))
+    def __init__(self, row_scale=None, pair_op: int = PAIR_NONE, rope_cos=None, rope_sin=None, residual=None,
+                 sq_in=None, sq_parts: int = 0, sq_eps: float = 0.0, sq_out=None):
+        self.keep = (row_scale, rope_cos, rope_sin, residual, sq_in, sq_out)
+        self.struct = _EpilogueStruct(_ptr(row_scale), pair_op, _ptr(rope_cos), _ptr(rope_sin), _ptr(residual),
+                                      _ptr(sq_in), int(sq_parts), float(sq_eps), _ptr(sq_out))
 
 
 class LayerPlanFused:

@@ -470,6 +470,10 @@ static mlora_status enqueue_call(const mlora_w4_proj *projs, int32_t n_proj, con
                 a->epi[i].rope_sin = e.rope_sin;
                 a->epi[i].residual = reinterpret_cast<const uint16_t *>(e.residual);
                 a->epi[i].pair_op = e.pair_op;
+                a->epi[i].sq_in = e.sq_in;
+                a->epi[i].sq_parts = e.sq_parts;
+                a->epi[i].sq_eps = e.sq_eps;
+                a->epi[i].sq_out = e.sq_out;
             }
         }
         a->y_fp32 = (y_dtype == MLORA_Y_FP32);
@@ -554,6 +558,9 @@ mlora_status mlora_w4_layer_step_fused(const mlora_w4_proj *projs, const mlora_w
         if (e.pair_op != MLORA_PAIR_NONE && e.pair_op != MLORA_PAIR_ROPE && e.pair_op != MLORA_PAIR_SWIGLU) return MLORA_EINVAL;
         if (e.pair_op != MLORA_PAIR_NONE && projs[i].N % TILE_N != 0) return MLORA_ESHAPE;
         if (e.pair_op == MLORA_PAIR_ROPE && (!e.rope_cos || !e.rope_sin)) return MLORA_EINVAL;
+        if (e.sq_in && (e.row_scale || e.sq_parts < 1 || !(e.sq_eps >= 0.0f))) return MLORA_EINVAL;
+        if ((e.sq_in && (reinterpret_cast<uintptr_t>(e.sq_in) & 3u)) ||
+            (e.sq_out && (reinterpret_cast<uintptr_t>(e.sq_out) & 3u))) return MLORA_EALIGN;
         if ((e.row_scale && (reinterpret_cast<uintptr_t>(e.row_scale) & 3u)) ||
             (e.rope_cos && (reinterpret_cast<uintptr_t>(e.rope_cos) & 3u)) ||
             (e.rope_sin && (reinterpret_cast<uintptr_t>(e.rope_sin) & 3u)) ||

@@ -108,7 +108,9 @@ constexpr int SPIN_LIMIT_DEFAULT = 200000;     // x ~0.5 us: far beyond any laun
 
 // What a fused call does to the outputs of a projection before they are stored (all optional):
 //   v = row_scale[m] * (base + LoRA term); a pair operation on columns (c, c + 32) of every
-//   64-column tile; + residual[m][n].
+//   64-column tile; + residual[m][n].  The row scale is either handed in or made from sq_in,
+//   the per-tile sums of squares that the projection which produced x left in its sq_out: the
+//   RMSNorm between two projections then needs no kernel of its own.
 // Pair operations: PAIR_ROPE rotates (v[c], v[c+32]) by the angle whose cosine and sine are
 // rope_cos/sin[m][c % 32] (heads of 64 features: a tile is a head); PAIR_SWIGLU stores
 // silu(v[c]) * v[c+32] at column 32 * tile + c % 32 of an output of N / 2 columns (the weight
@@ -119,7 +121,12 @@ struct EpiArgs {
     const float *rope_cos;         // fp32 [M][32]
     const float *rope_sin;
     const uint16_t *residual;      // bf16 [M][N_out]
+    const float *sq_in;            // fp32 [M][sq_parts]: partial sums of squares of the rows of x (another
+                                   // projection's sq_out); row scale = 1 / sqrt(sum / K + sq_eps)
+    float *sq_out;                 // fp32 [M][tiles]: sum of squares of the outputs a tile stores, as stored
     int pair_op;
+    int sq_parts;
+    float sq_eps;
     int pad_;
 };
 

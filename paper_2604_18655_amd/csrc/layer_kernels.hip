@@ -412,54 +412,115 @@ struct EpiPrefetch {
     }
 };
 
+// sum over the 16 lanes of a row of lanes (DPP rotations, fixed order); every lane gets the result
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xF, 0xF, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x122, 0xF, 0xF, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x121, 0xF, 0xF, false));
+    return v;
+}
+
 // Outputs of a fused call: the four values a lane holds of one row, columns 16 * j + l16 of a
 // tile (so (v[0], v[2]) and (v[1], v[3]) are the pairs 32 columns apart), go through the
-// projection's EpiArgs and are stored one by one.
-__device__ __forceinline__ void store_fused(const LayerArgs &a, const ProjArgs &P, int pi, int m, int tile, int l16,
-                                            float (&v)[4])
+// projection's EpiArgs and are stored one by one.  The 16 lanes that differ in l16 only hold the
+// same row and reach these calls together (m does not depend on l16): they share the sums over a
+// row.  What the output stage reads from memory is fetched by fused_fetch, which a caller may
+// issue well before the values are there (the loads then overlap what else it waits for).
+struct FusedOperands {
+    float scale_or_sum;            // row_scale[m], or this lane's share of the sums of squares
+    float cs[2], sn[2];            // rotary cosines and sines of the lane's two pairs
+    float res[4];                  // residual of the lane's four (SwiGLU: two) outputs
+};
+
+__device__ __forceinline__ FusedOperands fused_fetch(const LayerArgs &a, const ProjArgs &P, int pi, int m, int tile, int l16)
+{
+    FusedOperands f;
+    const EpiArgs &E = a.epi[pi];
+    const int mm = min(m, a.M - 1);                        // (rows past the end fetch a valid row and store nothing)
+    f.scale_or_sum = 1.0f;
+    if (E.row_scale) f.scale_or_sum = E.row_scale[mm];
+    if (E.sq_in) {
+        float sum = 0.f;
+        for (int p = l16; p < E.sq_parts; p += 16) sum += E.sq_in[(size_t)mm * E.sq_parts + p];
+        f.scale_or_sum = sum;
+    }
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+        f.cs[jj] = 1.0f;
+        f.sn[jj] = 0.0f;
+        if (E.pair_op == PAIR_ROPE) {
+            f.cs[jj] = E.rope_cos[(size_t)mm * 32 + 16 * jj + l16];
+            f.sn[jj] = E.rope_sin[(size_t)mm * 32 + 16 * jj + l16];
+        }
+    }
+    const int n_out = E.pair_op == PAIR_SWIGLU ? P.N >> 1 : P.N;
+    const int n0 = tile * (E.pair_op == PAIR_SWIGLU ? TILE_N / 2 : TILE_N) + l16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f.res[j] = 0.0f;
+        if (E.residual && (E.pair_op != PAIR_SWIGLU || j < 2))
+            f.res[j] = bf16_bits_to_float(E.residual[(size_t)mm * n_out + min(n0 + 16 * j, n_out - 1)]);
+    }
+    return f;
+}
+
+__device__ __forceinline__ void fused_store(const LayerArgs &a, const ProjArgs &P, int pi, int m, int tile, int l16,
+                                            const FusedOperands &f, float (&v)[4])
 {
     if (m >= a.M) return;
     const EpiArgs &E = a.epi[pi];
-    if (E.row_scale) {
-        const float rs = E.row_scale[m];
+    float rs = f.scale_or_sum;
+    if (E.sq_in) rs = 1.0f / sqrtf(row_sum16(f.scale_or_sum) / (float)P.K + E.sq_eps);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] *= rs;
-    }
+    for (int j = 0; j < 4; ++j) v[j] *= rs;
     const int N = P.N;
+    float sq = 0.f;                                        // squares of what this lane stores
+    auto put = [&](size_t at, float o) {
+        if (a.y_fp32) {
+            reinterpret_cast<float *>(P.y)[at] = o;
+        } else {
+            const uint16_t h = float_to_bf16_bits(o);
+            reinterpret_cast<uint16_t *>(P.y)[at] = h;
+            o = bf16_bits_to_float(h);
+        }
+        sq = fmaf(o, o, sq);
+    };
     if (E.pair_op == PAIR_SWIGLU) {
         const int n_out = N >> 1;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int n = tile * (TILE_N / 2) + 16 * jj + l16;
-            if (n >= n_out) continue;
             const float g = v[jj];
-            float o = g / (1.0f + expf(-g)) * v[jj + 2];
-            const size_t at = (size_t)m * n_out + n;
-            if (E.residual) o += bf16_bits_to_float(E.residual[at]);
-            if (a.y_fp32) reinterpret_cast<float *>(P.y)[at] = o;
-            else reinterpret_cast<uint16_t *>(P.y)[at] = float_to_bf16_bits(o);
+            if (n < n_out) put((size_t)m * n_out + n, g / (1.0f + expf(-g)) * v[jj + 2] + f.res[jj]);
         }
-        return;
-    }
-    if (E.pair_op == PAIR_ROPE) {
+    } else {
+        if (E.pair_op == PAIR_ROPE) {
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const float c = E.rope_cos[(size_t)m * 32 + 16 * jj + l16], sn = E.rope_sin[(size_t)m * 32 + 16 * jj + l16];
-            const float x0 = v[jj], x1 = v[jj + 2];
-            v[jj] = x0 * c - x1 * sn;
-            v[jj + 2] = x1 * c + x0 * sn;
+            for (int jj = 0; jj < 2; ++jj) {
+                const float x0 = v[jj], x1 = v[jj + 2];
+                v[jj] = x0 * f.cs[jj] - x1 * f.sn[jj];
+                v[jj + 2] = x1 * f.cs[jj] + x0 * f.sn[jj];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = tile * TILE_N + 16 * j + l16;
+            if (n < N) put((size_t)m * N + n, v[j] + f.res[j]);
         }
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int n = tile * TILE_N + 16 * j + l16;
-        if (n >= N) continue;
-        const size_t at = (size_t)m * N + n;
-        float o = v[j];
-        if (E.residual) o += bf16_bits_to_float(E.residual[at]);
-        if (a.y_fp32) reinterpret_cast<float *>(P.y)[at] = o;
-        else reinterpret_cast<uint16_t *>(P.y)[at] = float_to_bf16_bits(o);
+    if (E.sq_out) {
+        sq = row_sum16(sq);
+        if (l16 == 0) E.sq_out[(size_t)m * tiles_n(N) + tile] = sq;
     }
+}
+
+__device__ __forceinline__ void store_fused(const LayerArgs &a, const ProjArgs &P, int pi, int m, int tile, int l16,
+                                            float (&v)[4])
+{
+    const FusedOperands f = fused_fetch(a, P, pi, m, tile, l16);
+    fused_store(a, P, pi, m, tile, l16, f, v);
 }
 
 // the epilogue prefetch covers ranks up to this: 16 in the kernels for up to 16 rows (their register
@@ -757,6 +818,13 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const bool lean = PREFETCH && ku == 0 && (!lora || fast) && P.ksplit <= PU + 1;
     if (lean) {
         if constexpr (PREFETCH) {
+            // a fused call's operands of the output stage: on their way while t and the partial
+            // tiles are fetched
+            FusedOperands fo[MB];
+            if (a.fused) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) fo[mb] = fused_fetch(a, P, pi, m0 + elem_ml(4 * mb), tile, l16);
+            }
             if (lora) t_entries_to_lds();
             float pv[EPT][PU];
             if (P.ksplit > 1) {
@@ -822,7 +890,7 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
                 for (int j = 0; j < 4; ++j) v[j] = poisoned ? nan_f : v[j];
                 if (a.fused) {
                     float vv[4] = {v[0], v[1], v[2], v[3]};
-                    store_fused(a, P, pi, m, tile, l16, vv);
+                    fused_store(a, P, pi, m, tile, l16, fo[mb], vv);
                 } else if (m < M) {
                     if (a.y_fp32) {
                         float *yp = reinterpret_cast<float *>(P.y) + (size_t)m * N + n0;

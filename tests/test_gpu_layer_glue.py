@@ -23,14 +23,18 @@ def run_fused(gpu, probs, xs, rows, M, y_dtype, specs):
     lib, device, torch = gpu
     projs = [device.upload_problem(p) for p in probs]
     dxs = [device.to_device(x) for x in xs]
-    epis, ys = [], []
+    epis, ys, sq_outs = [], [], []
     for p, sp in zip(probs, specs):
         pair = {"none": lib.PAIR_NONE, "rope": lib.PAIR_ROPE, "swiglu": lib.PAIR_SWIGLU}[sp.get("pair", "none")]
+        sq_out = torch.full((M, -(-p.shape.N // 64)), -1.0, dtype=torch.float32, device="cuda") if sp.get("want_sq") else None
+        sq_outs.append(sq_out)
         epis.append(lib.Epilogue(
             None if sp.get("row_scale") is None else dev_f32(torch, sp["row_scale"]), pair,
             None if sp.get("cos") is None else dev_f32(torch, sp["cos"]),
             None if sp.get("sin") is None else dev_f32(torch, sp["sin"]),
-            None if sp.get("residual") is None else device.to_device(sp["residual"])))
+            None if sp.get("residual") is None else device.to_device(sp["residual"]),
+            None if sp.get("sq_in") is None else dev_f32(torch, sp["sq_in"]),
+            0 if sp.get("sq_in") is None else sp["sq_in"].shape[1], sp.get("sq_eps", 0.0), sq_out))
         n_out = p.shape.N // 2 if pair == lib.PAIR_SWIGLU else p.shape.N
         ys.append(device.alloc_y(M, n_out, y_dtype))
     ra = None if rows is None else torch.from_numpy(np.ascontiguousarray(rows, np.int32)).cuda()
@@ -38,6 +42,9 @@ def run_fused(gpu, probs, xs, rows, M, y_dtype, specs):
     lib.LayerPlanFused(projs, epis, dxs, ys, ra, M, y_dtype, ws).run()
     torch.cuda.synchronize()
     assert lib.workspace_status(ws) == 0
+    for sp, sq in zip(specs, sq_outs):
+        if sq is not None:
+            sp["got_sq"] = sq.cpu().numpy().astype(np.float64)
     return [device.y_to_numpy(y) for y in ys]
 
 
@@ -47,7 +54,7 @@ def reference(probs, xs, rows, specs):
         s = p.shape
         out.append(glue.fused_linear(p.wq, p.scales, s.group, p.lora_a, p.lora_b, s.alpha, x, rows,
                                      sp.get("row_scale"), sp.get("pair", "none"), sp.get("cos"), sp.get("sin"),
-                                     sp.get("residual")))
+                                     sp.get("residual"), sp.get("sq_in"), sp.get("sq_eps", 0.0)))
     return out
 
 
@@ -127,6 +134,42 @@ def test_fused_outputs_in_a_long_launch_of_17_to_32_rows(gpu):
     got = run_fused(gpu, probs, [x] * 10, rows, M, 1, specs)
     for i in range(10):
         assert rel_err(got[i], ref[i]) <= TOL_F32, (i, rel_err(got[i], ref[i]))
+
+
+@pytest.mark.parametrize("M", [5, 16, 30, 64])
+def test_sums_of_squares_in_and_out(gpu, M):
+    """RMSNorm without a kernel of its own: a projection leaves the sums of squares of its stored
+    outputs per column tile, and the projection that reads those outputs scales its rows with
+    them.  The sums are compared with the squares of the very outputs the device stored, the
+    consumer with the oracle fed with the device's sums."""
+    rng = np.random.default_rng(40 + M)
+    K = 512
+    pa = wl.make_problem(wl.ProjShape("o", K, 200, 32, 16, 3, 2.0), 2600 + M, 0, 0)      # 4 tiles, the last one ragged
+    pg = wl.make_problem(wl.ProjShape("gate", K, 64, 32, 8, 3, 2.0), 2600 + M, 0, 1)
+    pu = wl.make_problem(wl.ProjShape("up", K, 64, 32, 8, 3, 2.0), 2600 + M, 0, 2)
+    x = wl.make_x(M, K, 2600 + M, 0, 0)
+    rows = rng.integers(-1, 3, M).astype(np.int32)
+    res = f32_to_bf16_bits(rng.standard_normal((M, 200)).astype(np.float32))
+    for y_dtype in (1, 0):                            # (bf16 last: its outputs are the next projection's x below)
+        specs = [dict(residual=res, want_sq=True), dict(pair="swiglu", want_sq=True)]
+        probs = [pa, wl.fuse_gate_up(pg, pu)]
+        got = run_fused(gpu, probs, [x, x], rows, M, y_dtype, specs)
+        for i in range(2):
+            want = glue.tile_squares(got[i], 64 if i == 0 else 32)       # a SwiGLU tile stores 32 columns
+            assert specs[i]["got_sq"].shape == want.shape
+            assert np.max(np.abs(specs[i]["got_sq"] - want)) <= 1e-5 * np.max(want), (M, i, y_dtype)
+    # consumer: a projection whose x are the 200 columns the first one stored (padded to K = 256 with zeros)
+    sq = specs[0]["got_sq"].astype(np.float32)
+    pc = wl.make_problem(wl.ProjShape("c", 256, 128, 32, 16, 3, 2.0), 2600 + M, 0, 3)
+    x2 = np.zeros((M, 256), np.uint16)
+    x2[:, :200] = f32_to_bf16_bits(got[0].astype(np.float32))
+    spec = [dict(sq_in=sq, sq_eps=1e-5, pair="rope", cos=np.ones((M, 32), np.float32), sin=np.zeros((M, 32), np.float32))]
+    ref = reference([pc], [x2], rows, spec)
+    out = run_fused(gpu, [pc], [x2], rows, M, 1, spec)
+    assert rel_err(out[0], ref[0]) <= TOL_F32
+    # and the scale those sums give is the scale of the stored rows
+    direct = glue.rms_scale(bf16_bits_to_f32(x2).astype(np.float64), 1e-5)
+    assert np.max(np.abs(glue.scale_from_parts(sq, 256, 1e-5) / direct - 1)) <= 1e-5
 
 
 def test_rms_scale_matches_oracle(gpu):
@@ -226,12 +269,15 @@ def test_decoder_layer_every_stage_and_end_to_end(gpu, S, branch):
     assert rel_err(f64(attn), att(q, k, v)) <= TOL
     h2 = bits_of(layer.h2)
     assert rel_err(f64(h2), lin("o", attn, residual_bits=h)) <= TOL
-    s2 = layer.s2.cpu().numpy()
-    assert np.max(np.abs(s2 / glue.rms_scale(f64(h2), 1e-5) - 1)) <= 1e-5
+    sq2 = layer.sq2.cpu().numpy()                                    # left by the o projection, per column tile
+    assert np.max(np.abs(sq2 - glue.tile_squares(f64(h2)))) <= 1e-5 * np.max(sq2)
+    assert np.max(np.abs(glue.scale_from_parts(sq2, Hq * 64, 1e-5) / glue.rms_scale(f64(h2), 1e-5) - 1)) <= 1e-5
     act = bits_of(layer.act)
-    assert rel_err(f64(act), lin("gate_up", h2, row_scale=s2, pair_op="swiglu")) <= TOL
+    assert rel_err(f64(act), lin("gate_up", h2, sq_in=sq2, sq_eps=1e-5, pair_op="swiglu")) <= TOL
     out = bits_of(layer.out)
     assert rel_err(f64(out), lin("down", act, residual_bits=h2)) <= TOL
+    out_sq = layer.out_sq.cpu().numpy()                              # for the next layer's first normalisation
+    assert np.max(np.abs(out_sq - glue.tile_squares(f64(out)))) <= 1e-5 * np.max(out_sq)
 
     # the oracle's own chain, end to end
     rb = lambda y: f32_to_bf16_bits(y.astype(np.float32))

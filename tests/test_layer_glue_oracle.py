@@ -98,3 +98,14 @@ def test_fused_linear_order_of_operations():
     assert np.allclose(got, want, rtol=1e-13)
     # the scale commutes with the rotation, the residual does not
     assert not np.allclose(got, glue.rope(y * s[:, None] + 0.25, np.cos(ang), np.sin(ang)))
+
+
+def test_scale_from_partial_sums_of_squares_equals_the_direct_scale():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((6, 200))
+    parts = glue.tile_squares(x)                                   # runs of 64 columns, the last one short
+    assert parts.shape == (6, 4) and np.isclose(parts[2, 3], np.sum(x[2, 192:] ** 2))
+    assert np.allclose(glue.scale_from_parts(parts, 200, 1e-5), glue.rms_scale(x, 1e-5), rtol=1e-14)
+    # any partition of a row gives the same scale
+    other = np.stack([np.sum(x[:, :7] ** 2, axis=1), np.sum(x[:, 7:] ** 2, axis=1)], axis=1)
+    assert np.allclose(glue.scale_from_parts(other, 200, 1e-5), glue.rms_scale(x, 1e-5), rtol=1e-14)
