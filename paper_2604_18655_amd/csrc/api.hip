@@ -247,7 +247,9 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
             // base blocks: one per column tile, or per four of them in the wide kernel
             const int col_blocks = (tiles + tiles_per_block(wide) - 1) / tiles_per_block(wide);
             const size_t part_bytes = partial_bytes(p, M, wide, lb);
-            const int kch = kch_of(p, Mc);
+            // (two chunks of 16 rows have twice the rows of the shapes the per-row shrink blocks were
+            // laid out for: at most 4 K chunks then, which also keeps the sum over them on its short path)
+            const int kch = chunk16 && kch_of(p, Mc) > 4 ? 4 : kch_of(p, Mc);
             const size_t t_bytes = lora ? round_up((size_t)kch * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256) : 0;
             const int n_shrink = !lora ? 0
                 : (Mc <= 16 && !wide ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *

@@ -74,8 +74,9 @@ def test_workspace_bytes():
     # units of 4 x 128 inputs; the shrink step leaves 16 chunks of partial sums)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == need(lines(1, 1), 16 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == need(lines(1, 1), 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
-    # (17 to 32 rows: one chunk of 32 rows, 8 units of 2048 inputs)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == need(lines(1, 1), 16 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4)
+    # (17 to 32 rows, a short launch: two chunks of 16 rows, 8 units of 2048 inputs, a shrink block
+    # per row with at most 4 K chunks)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == need(lines(1, 2), 4 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4)
     # a launch of the 64-row kernel with 80 to 240 base blocks gets K units of 8 x 128 inputs:
     # K = 3072, N = 8192 (128 tiles = 32 blocks of columns), 128 rows (2 chunks) -> 3 units
     p = proj(K=3072, N=8192, group=64, rank=16)
