@@ -237,7 +237,7 @@ constexpr int WIDE_ALWAYS_ROWS = 33;
 constexpr int WIDE32_MIN_ROWS = 17;
 constexpr int WIDE32_MIN_BLOCKS = 300;
 constexpr int WIDE_TILES_PER_BLOCK = 4;
-constexpr int CHUNK16_MAX_BLOCKS = 200;    // tile launches of 17 to 32 rows below this run chunks of 16 rows
+constexpr int CHUNK16_MAX_BLOCKS = 300;    // tile launches of 17 to 32 rows below this run chunks of 16 rows
 __host__ __device__ inline int rows_per_chunk(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : 64; }
 // column tiles a base block covers
 __host__ __device__ inline int tiles_per_block(bool wide) { return wide ? WIDE_TILES_PER_BLOCK : 1; }
