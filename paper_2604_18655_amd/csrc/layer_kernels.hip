@@ -570,7 +570,7 @@ __device__ __forceinline__ float dot8(uint4 b8, const float *t, float l)
 // row block mb and column block j, the rows 16*mb + 4*(l/16) + e (e = 0..3) of column 16*j + l%16;
 // thread (wave w, lane l) finishes e = w of every (mb, j): EPT = 4*MB outputs that lie in MB rows
 // (one adapter each), 16 columns apart.
-template <int MB, int XR, int WAVES, int R>
+template <int MB, int XR, int WAVES, int R, int FR>
 __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P, int pi, int tile, int ku,
                                  int m0, const BaseLds<MB, XR, WAVES, R> &lds)
 {
@@ -603,7 +603,6 @@ __device__ __forceinline__ void base_unit(const LayerArgs &a, const ProjArgs &P,
     const int rows_here = min(ROWS, M - m0);
     constexpr bool PREFETCH = EPT <= 8;                    // more outputs per thread: too many registers
     // (ranks up to FR: the entries of t of a chunk number at most MB * FR / 16 per thread)
-    constexpr int FR = fast_rank<MB>();
     const bool fast = PREFETCH && lora && P.rank <= FR;
     // element qq of this thread: tile row and column (cheap to recompute, so not kept live)
     static_assert(WAVES == 4, "one wave per element of an MFMA result register");
@@ -1431,7 +1430,16 @@ __global__ __launch_bounds__(64 * Shape<MB>::WAVES, (occupancy_of<MB, XR>())) vo
     const int tiles = tiles_n(P.N);
     // local / tiles (tiles_inv = ceil(2^32 / tiles) does not fit 32 bits for a single tile)
     const int unit = !pre ? 0 : tiles == 1 ? local : (int)__umulhi((unsigned)local, P.tiles_inv);
-    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R>(a, P, pi, local - unit * tiles, pre ? 1 + unit : 0, m0, lds);
+    // (the kernel for 9 to 16 rows also runs the 16-row chunks of short launches of up to 32 rows,
+    // among them a fused gate/up projection with its LoRA pair of twice the rank: a second copy of
+    // the block with the prefetch for ranks up to 32; a call of rank 16 runs the code it always ran)
+    if constexpr (MB == 1 && XR == 16) {
+        if (P.rank > fast_rank<MB>()) {
+            base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R, 32>(a, P, pi, local - unit * tiles, pre ? 1 + unit : 0, m0, lds);
+            return;
+        }
+    }
+    base_unit<MB, XR, Shape<MB>::WAVES, Shape<MB>::R, fast_rank<MB>()>(a, P, pi, local - unit * tiles, pre ? 1 + unit : 0, m0, lds);
 }
 
 // ------------------------------------------------------------------------------------------
