@@ -74,6 +74,19 @@ __device__ __forceinline__ void shared16_wait(f32x4_t (&v)[16])
                  :
                  : "memory");
 }
+// 16-byte loads of such data that the compiler can see (and so schedule, and wait for, by
+// itself): buffer loads with the same cache policy (sc1, bit 4 of the policy argument) through a
+// descriptor over `bytes` bytes at `base` (raw buffer, no stride; accesses past the end return 0).
+// `base` and `bytes` must be the same for every lane of a wave.
+typedef unsigned int u32x4_v __attribute__((vector_size(16)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t shared_buffer(const float *base, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ f32x4_t load_shared16(__amdgpu_buffer_rsrc_t rsrc, int byte_offset)
+{
+    return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 16));
+}
 
 // The hardware keeps the order "data, then counter" on the producer's side (the wait for the
 // stores' acknowledgements below) and "counter, then data" on the consumer's (a wave's loads are
@@ -2042,16 +2055,35 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
             poisoned = true;
             if (lane == 0) atomicOr(a.status, 1u);
         }
-        for (int u = 0; u + 1 < P.ksplit; ++u) {
-            const float *src = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0) * TILE_N + lane * 4;
-            f32x4_t pv[4 * MB];
+        // The other units' partial tiles, added in the order of the units.  Two sets of registers:
+        // a unit's tile is added while the next one is on its way (a projection with a long K has
+        // a dozen of them, and one round trip after another was most of its finishing block's time).
+        // These are loads the compiler sees (it places the waits): values it does not know to be
+        // in flight must not stay in registers across other code, which it may spill or reuse.
+        constexpr int NP = 4 * MB;
+        const int np = P.ksplit - 1;
+        auto request = [&](f32x4_t (&pv)[NP], int u) {
+            // (the tile of unit u for this wave's chunk: NP KiB, the same place for all lanes)
+            const float *base = P.partial + (((size_t)u * tiles + tile) * a.m_pad + m0) * TILE_N;
+            const __amdgpu_buffer_rsrc_t rsrc = shared_buffer(base, NP * 1024);
 #pragma unroll
-            for (int i = 0; i < 4 * MB; ++i) pv[i] = load_shared16(src + i * 256);
-            shared16_wait(pv);
+            for (int i = 0; i < NP; ++i) pv[i] = load_shared16(rsrc, lane * 16 + i * 1024);
+        };
+        auto fold = [&](const f32x4_t (&pv)[NP]) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[mb][j] += pv[mb * 4 + j];
+        };
+        f32x4_t pa[NP], pb[NP];
+        if (np > 0) request(pa, 0);
+        for (int u = 0; u < np; u += 2) {
+            if (u + 1 < np) request(pb, u + 1);
+            fold(pa);
+            if (u + 1 < np) {
+                if (u + 2 < np) request(pa, u + 2);
+                fold(pb);
+            }
         }
     }
     if (poisoned) {
