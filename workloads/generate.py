@@ -129,6 +129,44 @@ def make_x_int8(M: int, K: int, cfg_id: int, layer: int, slot_index: int) -> Tup
     return quantise_act_int8(x)
 
 
+def quantise_lora_int16(t: np.ndarray) -> Tuple[np.ndarray, np.float32]:
+    """Symmetric int16 quantisation of a stack of LoRA tensors with ONE scale for the stack:
+    s = max|t| / 32767 in float32 (1 for an all-zero stack), round to nearest even, clamp."""
+    t = np.asarray(t, np.float32)
+    top = np.float32(np.max(np.abs(t))) if t.size else np.float32(0)
+    scale = np.float32(top / np.float32(32767.0)) if top > 0 else np.float32(1.0)
+    q = np.clip(np.rint(t / scale), -32767, 32767).astype(np.int16)
+    return q, scale
+
+
+@dataclass
+class ProblemLoraInt16:
+    """A projection whose LoRA tensors are int16 with one scale per stack (the base weight as in Problem)."""
+    shape: ProjShape
+    wq: np.ndarray        # uint8  [N][K/2]
+    scales: np.ndarray    # uint16 [N][K/group]  (fp16 bits)
+    aq: np.ndarray        # int16 [n_adapters][rank][K]
+    s_a: np.float32
+    bq: np.ndarray        # int16 [n_adapters][N][rank]
+    s_b: np.float32
+
+
+def make_problem_lora_int16(shape: ProjShape, cfg_id: int, layer: int, proj_index: int) -> ProblemLoraInt16:
+    """The tensors of make_problem with the LoRA stacks quantised to int16 instead of rounded to bf16."""
+    p = shape
+    w = _rng(cfg_id, layer, proj_index, T_W).standard_normal((p.N, p.K), dtype=np.float32)
+    w *= np.float32(0.02)
+    wq, scales = quantise_int4(w, p.group)
+    del w
+    a = _rng(cfg_id, layer, proj_index, T_A).standard_normal((p.n_adapters, p.rank, p.K), dtype=np.float32)
+    a *= np.float32(1.0 / np.sqrt(p.K))
+    b = _rng(cfg_id, layer, proj_index, T_B).standard_normal((p.n_adapters, p.N, p.rank), dtype=np.float32)
+    b *= np.float32(0.01)
+    aq, s_a = quantise_lora_int16(a)
+    bq, s_b = quantise_lora_int16(b)
+    return ProblemLoraInt16(p, wq, scales, aq, s_a, bq, s_b)
+
+
 def make_rows(row_map: str, M: int, n_adapters: int, cfg_id: int = 0) -> np.ndarray:
     """Row -> adapter index (int32 [M]).
 
