@@ -60,6 +60,9 @@ def parse_args():
                          "known traffic next to which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings "
                          "of the layer kernel can be scaled")
     ap.add_argument("--y-fp32", action="store_true")
+    ap.add_argument("--lora-int16", action="store_true",
+                    help="LoRA stacks stored as int16 with one scale per stack, expanded by the library into a "
+                         "bf16 pair of four times the rank (layer-step workloads c1..c5, not with --a8)")
     ap.add_argument("--a8", action="store_true",
                     help="int8 activations with one scale per tensor (mlora_w4a8_layer_step) instead of bf16")
     return ap.parse_args()
@@ -298,7 +301,7 @@ def bench_layer(args):
         "us_per_step": round(elapsed * 1e6 / K, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_step": int(step_bytes), "max_rel_err": float(f"{max_rel_err:.3e}"),
         "setup_s": round(setup_s, 1),
-        "roofline": {"kernel": "layer_kernel<1, 16> x 3 + layer_kernel<2, 32> + tree_attn_partial/combine + rms_scale_kernel (one step)",
+        "roofline": {"kernel": "layer_kernel<1, 16> x 4 + tree_attn_partial/combine + rms_scale_kernel (one step)",
                      "bound": "hbm", "achieved": round(step_bytes / step_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(step_bytes / step_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": int(step_bytes), "avg_launch_us": round(step_s * 1e6, 3),
@@ -431,6 +434,9 @@ def main():
         print("bench.py: this build runs on one GPU only (the path shards along N, see DESIGN.md); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.a8 and args.lora_int16:
+        print("bench.py: --a8 and --lora-int16 are separate variants", file=sys.stderr)
+        sys.exit(2)
     if args.workload == "c4_ds2d":
         bench_ds2d(args)
         return
@@ -473,8 +479,13 @@ def main():
     for c in range(copies):
         projs, dxs, ys, x_scales = [], [], [], []
         for layer in range(w.layers):
-            probs, xs, rows = wl.make_layer(w, layer=c * w.layers + layer)
-            projs += [device.upload_problem(p, dev) for p in probs]
+            if args.lora_int16:
+                probs = [wl.make_problem_lora_int16(s_, w.cfg_id, c * w.layers + layer, i) for i, s_ in enumerate(w.projs)]
+                _, xs, rows = wl.make_layer_inputs(w, layer=c * w.layers + layer)
+                projs += [device.upload_problem_lora_int16(p, dev) for p in probs]
+            else:
+                probs, xs, rows = wl.make_layer(w, layer=c * w.layers + layer)
+                projs += [device.upload_problem(p, dev) for p in probs]
             cache = {}
             if args.a8:
                 xs = list(xs)
@@ -590,6 +601,7 @@ def main():
     for ws in workspaces:
         assert lib.workspace_status(ws) == 0, "a block gave up waiting for another: results invalid"
     import oracle
+    from oracle import lora_int16 as lora_int16_oracle
     probs0, xs0, rows_h = host_layer0
     max_rel_err = 0.0
     sample = list(range(n_proj)) if M <= 64 else [0, n_proj - 1]
@@ -599,6 +611,9 @@ def main():
         if args.a8:
             ref = oracle.linear_a8(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
                                    np.ascontiguousarray(xs0[i][msel]), host_scales0[i], np.ascontiguousarray(rows_h[msel]))
+        elif args.lora_int16:
+            ref = lora_int16_oracle.linear(p.wq, p.scales, p.shape.group, p.aq, p.s_a, p.bq, p.s_b, p.shape.alpha,
+                                           np.ascontiguousarray(xs0[i][msel]), np.ascontiguousarray(rows_h[msel]))
         else:
             ref = oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha,
                                 np.ascontiguousarray(xs0[i][msel]), np.ascontiguousarray(rows_h[msel]))
@@ -623,7 +638,7 @@ def main():
     kernel_tag = ("wide_kernel_a8" if args.a8 else "wide_kernel") if wide else "layer_kernel"
     achieved_tflops = (step_flops / launches_per_step) / kern_s / 1e12
     bound = BOUND.get(w.key, "hbm")
-    traffic, traffic_src = measured_traffic(kernel_tag, w.key) if not args.per_layer_calls else (None, None)
+    traffic, traffic_src = measured_traffic(kernel_tag, w.key) if not (args.per_layer_calls or args.lora_int16) else (None, None)
 
     result = {
         "metric": METRIC,
@@ -646,6 +661,8 @@ def main():
             "y_dtype": "fp32" if args.y_fp32 else "bf16", "x_dtype": "int8, one scale per tensor" if args.a8 else "bf16",
             "rotating_copies": copies, "launch_mode": args.mode,
             "calls_per_step": calls_per_step,
+            **({"lora": "int16 stacks, one scale each; served as a bf16 pair of rank %d (4x the bytes of the int16 "
+                        "tensors, which are what the algorithmic bytes count)" % (4 * w.projs[0].rank)} if args.lora_int16 else {}),
         },
         "us_per_step": round(ms_per_step * 1e3, 3),
         "us_per_linear": round(ms_per_step * 1e3 / (n_proj * w.layers), 3),
@@ -707,6 +724,8 @@ def main():
             for i, (p, x) in enumerate(zip(probs0, xs0)):
                 if args.a8:
                     oracle.linear_a8(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, host_scales0[i], rows_h)
+                elif args.lora_int16:
+                    lora_int16_oracle.linear(p.wq, p.scales, p.shape.group, p.aq, p.s_a, p.bq, p.s_b, p.shape.alpha, x, rows_h)
                 else:
                     oracle.linear(p.wq, p.scales, p.shape.group, p.lora_a, p.lora_b, p.shape.alpha, x, rows_h)
             t_cpu += time.perf_counter() - t1
@@ -720,7 +739,7 @@ def main():
                       f"{t_cpu:.1f} s of fp64 loops on {cores} threads",
             "us_per_linear": round(t_cpu / reps / len(probs0) * 1e6, 1),
         }
-        if w.key in ("c1", "c2", "c3") and not args.a8:
+        if w.key in ("c1", "c2", "c3") and not args.a8 and not args.lora_int16:
             # the small configurations also on ONE host thread (bounded the same way)
             oracle.set_threads(1)
             reps1, t1_cpu = 0, 0.0

@@ -200,6 +200,26 @@ mlora_status mlora_w4_layer_step_fused(const mlora_w4_proj *projs, const mlora_w
  * factor of RMSNorm, computed in fp32 in a fixed order.  x 16-byte aligned, scale fp32 [M]. */
 mlora_status mlora_rms_scale(const void *x, int32_t M, int32_t K, float eps, float *scale, void *stream);
 
+/* LoRA tensors stored as 16-bit integers (the appendix on the 1B model names int16 LoRA weights
+ * next to the int4 base weights), with one scale per stack:  A[a] = s_a * a_q[a],
+ * B[a] = s_b * b_q[a].  This call turns such a pair of stacks into the bf16 tensors and the alpha
+ * that mlora_w4_proj takes, without rounding anything: an int16 is 256 * hi + lo with digits that
+ * are bf16 numbers, so  b_q (a_q x) = (256 Bh + Bl) (256 (Ah x) + (Al x))  is the product of a
+ * LoRA pair of FOUR TIMES the rank,
+ *     lora_a  [n_adapters][4 * rank][K]:  rows  j, rank + j, 2 rank + j, 3 rank + j  = Ah, Ah, Al, Al of row j
+ *     lora_b  [n_adapters][N][4 * rank]:  columns likewise = 65536 Bh, 256 Bl, 256 Bh, Bl of column j
+ * and  *alpha_out = alpha * s_a * s_b  (fp32, written on the HOST before the call returns).  A
+ * projection then uses  {rank = 4 * rank, alpha = *alpha_out, lora_a, lora_b}:  the matrix units
+ * multiply exact integers, sums are fp32 as for bf16 adapters.  Cost: four times the bytes of the
+ * int16 tensors in the layer step; done once, when an adapter set is loaded.
+ *   a_q  DEVICE int16 [n_adapters][rank][K],  b_q  DEVICE int16 [n_adapters][N][rank]
+ *   lora_a, lora_b  DEVICE, caller-allocated, sizes as above (bf16), all four 16-byte aligned
+ *   rank % 8 == 0, 4 * rank <= MLORA_MAX_RANK;  K % 32 == 0;  s_a, s_b finite and > 0
+ * Errors (nothing is launched): MLORA_ESHAPE, MLORA_EINVAL, MLORA_EALIGN; MLORA_EHIP if a launch fails. */
+mlora_status mlora_lora_int16_expand(const int16_t *a_q, const int16_t *b_q, int32_t n_adapters, int32_t rank,
+                                     int32_t K, int32_t N, float alpha, float s_a, float s_b,
+                                     void *lora_a, void *lora_b, float *alpha_out, void *stream);
+
 /* The layer step with int8 activations (Section 3.3: activations quantised to int8 with one
  * scale per tensor, weights to int4).  As mlora_w4_layer_step, except that
  *   xs[i]        int8 [M][K]: the quantised rows; the activation they stand for is

@@ -19,7 +19,7 @@ exported_symbols = (
     "mlora_w4_layer_step_static", "mlora_w4_layer_step_plan",
     "mlora_tree_attention_workspace_bytes", "mlora_tree_attention",
     "mlora_w4a8_workspace_bytes", "mlora_w4a8_layer_step",
-    "mlora_w4_layer_step_fused", "mlora_rms_scale",
+    "mlora_w4_layer_step_fused", "mlora_rms_scale", "mlora_lora_int16_expand",
     "mlora_ds2d_rows", "mlora_ds2d_layout", "mlora_ds2d_workspace_bytes", "mlora_ds2d_step",
 )
 
@@ -109,6 +109,9 @@ def load_library():
                                                   vp, i32, i32, vp, sz, vp]
         lib.mlora_rms_scale.restype = C.c_int
         lib.mlora_rms_scale.argtypes = [vp, i32, i32, C.c_float, vp, vp]
+        lib.mlora_lora_int16_expand.restype = C.c_int
+        lib.mlora_lora_int16_expand.argtypes = [vp, vp, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
+                                                vp, vp, C.POINTER(C.c_float), vp]
         dp = C.POINTER(_Ds2dStruct)
         ip = C.POINTER(i32)
         lib.mlora_ds2d_rows.restype = C.c_int
@@ -299,6 +302,18 @@ class LayerPlanFused:
 def rms_scale(x, M: int, K: int, eps: float, scale, stream: Optional[int] = None) -> None:
     _check(load_library().mlora_rms_scale(_ptr(x), M, K, float(eps), _ptr(scale),
                                           _stream() if stream is None else stream), "mlora_rms_scale")
+
+
+def lora_int16_expand(a_q, b_q, n_adapters: int, rank: int, K: int, N: int, alpha: float, s_a: float, s_b: float,
+                      lora_a, lora_b, stream: Optional[int] = None) -> float:
+    """int16 LoRA stacks -> the bf16 tensors of a pair of four times the rank (written to lora_a,
+    lora_b); returns the alpha to use with them."""
+    alpha_out = C.c_float(0.0)
+    _check(load_library().mlora_lora_int16_expand(_ptr(a_q), _ptr(b_q), n_adapters, rank, K, N, float(alpha),
+                                                  float(s_a), float(s_b), _ptr(lora_a), _ptr(lora_b),
+                                                  C.byref(alpha_out), _stream() if stream is None else stream),
+           "mlora_lora_int16_expand")
+    return float(alpha_out.value)
 
 
 def a8_workspace_bytes(projs: Sequence[Proj], M: int) -> int:

@@ -1,6 +1,7 @@
 // C ABI of the mlora_w4 library: host-side validation, launch planning, no device allocation.
 #include <string.h>
 
+#include <cmath>
 #include <algorithm>
 #include <memory>
 #include <mutex>
@@ -591,6 +592,24 @@ mlora_status mlora_rms_scale(const void *x, int32_t M, int32_t K, float eps, flo
     if (!x || !scale || !(eps >= 0.0f)) return MLORA_EINVAL;
     if (!aligned16(x) || (reinterpret_cast<uintptr_t>(scale) & 3u)) return MLORA_EALIGN;
     return launch_rms_scale(reinterpret_cast<const uint16_t *>(x), M, K, eps, scale, (hipStream_t)stream) == hipSuccess
+               ? MLORA_OK : MLORA_EHIP;
+}
+
+mlora_status mlora_lora_int16_expand(const int16_t *a_q, const int16_t *b_q, int32_t n_adapters, int32_t rank,
+                                     int32_t K, int32_t N, float alpha, float s_a, float s_b,
+                                     void *lora_a, void *lora_b, float *alpha_out, void *stream)
+{
+    if (n_adapters < 1 || n_adapters > MLORA_MAX_ADAPTERS || rank <= 0 || rank % 8 != 0 || 4 * rank > MLORA_MAX_RANK)
+        return MLORA_ESHAPE;
+    if (K <= 0 || K % KSTEP != 0 || K > (1 << 24) || N <= 0 || N > (1 << 24)) return MLORA_ESHAPE;
+    const unsigned long long na = (unsigned long long)n_adapters * rank * K, nb = (unsigned long long)n_adapters * N * rank;
+    if ((na + 255) / 256 > 0x7FFFFFFFull || (nb + 255) / 256 > 0x7FFFFFFFull) return MLORA_ESHAPE;
+    if (!a_q || !b_q || !lora_a || !lora_b || !alpha_out) return MLORA_EINVAL;
+    if (!std::isfinite(alpha) || !std::isfinite(s_a) || !std::isfinite(s_b) || !(s_a > 0.0f) || !(s_b > 0.0f)) return MLORA_EINVAL;
+    if (!aligned16(a_q) || !aligned16(b_q) || !aligned16(lora_a) || !aligned16(lora_b)) return MLORA_EALIGN;
+    *alpha_out = alpha * s_a * s_b;
+    return launch_lora_int16_expand(a_q, b_q, n_adapters, rank, K, N, reinterpret_cast<uint16_t *>(lora_a),
+                                    reinterpret_cast<uint16_t *>(lora_b), (hipStream_t)stream) == hipSuccess
                ? MLORA_OK : MLORA_EHIP;
 }
 

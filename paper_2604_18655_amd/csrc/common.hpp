@@ -225,6 +225,8 @@ hipError_t launch_group_rows(const int *row_adapter, int M, int n_adapters, int 
 hipError_t launch_layer(const LayerArgs &a, int grid_x, int groups, hipStream_t s);
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 hipError_t launch_rms_scale(const uint16_t *x, int M, int K, float eps, float *scale, hipStream_t s);
+hipError_t launch_lora_int16_expand(const int16_t *aq, const int16_t *bq, int n_adapters, int rank, int K, int N,
+                                    uint16_t *a4, uint16_t *b4, hipStream_t s);
 
 constexpr int UNIT_SUPER_STEPS = 16;   // a block streams at most 16 super-steps (2048 inputs)
 // Two families of base blocks.  "Tile" blocks cover one column tile and their four waves split

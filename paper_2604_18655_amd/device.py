@@ -33,6 +33,23 @@ def upload_problem(problem, device="cuda:0", with_lora: bool = True) -> binding.
     return binding.Proj(s.K, s.N, s.group, blob, None, None, s.alpha)
 
 
+def upload_problem_lora_int16(problem, device="cuda:0") -> binding.Proj:
+    """problem: workloads.ProblemLoraInt16 (int16 LoRA stacks aq, bq with scales s_a, s_b).  The
+    library expands them into a bf16 pair of four times the rank and folds the scales into alpha."""
+    s = problem.shape
+    wq = to_device(problem.wq, device)
+    scales = to_device(problem.scales, device)
+    blob = torch.empty(binding.blob_bytes(s.K, s.N, s.group), dtype=torch.uint8, device=device)
+    binding.prepack(s.K, s.N, s.group, wq, scales, blob)
+    aq, bq = to_device(problem.aq, device), to_device(problem.bq, device)
+    lora_a = torch.empty((s.n_adapters, 4 * s.rank, s.K), dtype=torch.int16, device=device)
+    lora_b = torch.empty((s.n_adapters, s.N, 4 * s.rank), dtype=torch.int16, device=device)
+    alpha = binding.lora_int16_expand(aq, bq, s.n_adapters, s.rank, s.K, s.N, s.alpha, float(problem.s_a),
+                                      float(problem.s_b), lora_a, lora_b)
+    torch.cuda.synchronize()
+    return binding.Proj(s.K, s.N, s.group, blob, lora_a, lora_b, alpha)
+
+
 def alloc_y(M: int, N: int, y_dtype: int, device="cuda:0") -> torch.Tensor:
     return torch.empty((M, N), dtype=torch.float32 if y_dtype == binding.Y_FP32 else torch.int16,
                        device=device)
