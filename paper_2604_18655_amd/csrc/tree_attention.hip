@@ -331,14 +331,16 @@ __global__ __launch_bounds__(1024) void tree_attn_combine(const AttnArgs a)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Chunks a block walks through.  One, as long as that gives at most about a thousand blocks per
-// segment (blocks are short, and what bounds a call of this size is the latency of a block, not
-// the bytes it moves); longer runs for longer segments, so that what the blocks leave in the
-// workspace stays well below what they read.
+// Chunks a block walks through: as many as give about 128 blocks (per slice of query vectors) for
+// the longest segment, at most 16.  A block's result (64 vectors x 66 floats) is four times the
+// keys and values of a chunk it reads, and every one is read again by the merging kernel: with
+// one chunk per block a call of 2048 keys moved far more partial results than keys; two chunks
+// measured 5 % faster there, four slower (blocks are short, and what bounds a call of this size
+// is the chain of latencies inside a block).
 int chunks_per_block(int longest, int n_kv_heads)
 {
     const long long chunks = (longest + KC - 1) / KC;
-    const long long cpb = (chunks * n_kv_heads + 1023) / 1024;
+    const long long cpb = (chunks * n_kv_heads + 127) / 128;
     return cpb < 1 ? 1 : cpb > 16 ? 16 : (int)cpb;
 }
 

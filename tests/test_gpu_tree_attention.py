@@ -55,6 +55,7 @@ def check(gpu, inp, Hq, Hkv, D, tag):
     (3, "ds2d221", 5, 12, 2, 64, 0, 7, 0),          # no prefill, no stream cache: prefix and the step's rows only
     (4, "random64", 2, 6, 3, 128, 300, 64, 129),    # 64 rows per stream (the most), 2 heads per kv head
     (5, "chain1", 16, 8, 1, 64, 1000, 0, 33),       # one row per stream, 8 query heads on one kv head
+    (6, "chain4", 2, 8, 4, 64, 5000, 130, 300),     # three chunks of keys per block, a last block with one; 5 chunks of stream keys in 2 blocks
 ])
 def test_tree_attention_matches_oracle(gpu, seed, tree, S, Hq, Hkv, D, Lp, Lf, cap):
     rng = np.random.default_rng(seed)
