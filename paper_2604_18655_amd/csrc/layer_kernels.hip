@@ -1549,7 +1549,7 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp
     const int n_stages = (n_ksteps + S - 1) / S;
 
     // one stage: register sets [h * S, h * S + S), x buffer st & 1
-    auto stage = [&](auto half, int st) {
+    auto stage = [&](auto half, int st, auto full) {
         constexpr int H = decltype(half)::value;
         __syncthreads();                                   // this stage's rows of x are in place; the other buffer is free
         const int buf = (st & 1) * L::X_STAGE;
@@ -1580,14 +1580,6 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp
                         xk[t][mb] = *reinterpret_cast<const u32x4 *>(xfrag + buf + mb * 16 * L::XROW + (r * SG + t) * 64);
                         corr[mb] = mfma16(__builtin_bit_cast(uint4, xk[t][mb]), __builtin_bit_cast(uint4, neg24), corr[mb]);
                     }
-                u32x4 wv[SG];
-#pragma unroll
-                for (int t = 0; t < SG; ++t) {
-                    const int k = r * SG + t;              // k-step within the stage
-                    wv[t] = w[H * S + k];
-                    const int kc = min(st * S + k + W, last);
-                    w[H * S + k] = __builtin_nontemporal_load(wp + kc * 64);
-                }
                 constexpr int G0 = (H * S) / SPG;          // first scale group of this stage's register sets
                 const int g = (r * SG) / SPG;              // scale group of the run within the stage
                 const uint2 sv = sc[G0 + g];
@@ -1600,7 +1592,7 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp
                     f32x4 d[MB];
 #pragma unroll
                     for (int t = 0; t < SG; ++t) {
-                        const uint4 wb = expand_codes(wv[t][j], mask, bias);
+                        const uint4 wb = expand_codes(w[H * S + r * SG + t][j], mask, bias);
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb)
                             d[mb] = mfma16(__builtin_bit_cast(uint4, xk[t][mb]), wb, t == 0 ? corr[mb] : d[mb]);
@@ -1613,22 +1605,39 @@ __device__ __forceinline__ void stream_loop(f32x4 (&acc)[MB][4], const u32x4 *wp
 #pragma unroll
                         for (int e = 0; e < 4; ++e) acc[mb][j][e] = fmaf(d[mb][e], sj, acc[mb][j][e]);
                 }
+                // the run's register sets are used up: request their next k-steps (after the last
+                // use, so that no copy of the old contents has to be kept)
+#pragma unroll
+                for (int t = 0; t < SG; ++t) {
+                    const int k = r * SG + t;              // k-step within the stage
+                    const int kc = min(st * S + k + W, last);
+                    w[H * S + k] = __builtin_nontemporal_load(wp + kc * 64);
+                }
             }
         };
-        if constexpr (S > 4) {
-            if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
-            else                        stage_math(std::integral_constant<int, 4>{});
-        } else {
-            stage_math(std::integral_constant<int, S>{});  // (a unit is a whole number of 4-k-step stages)
-        }
+        // (a unit is a whole number of 4-k-step super-steps: a stage of 8 k-steps is full, or the
+        // unit's last one with 4)
+        if constexpr (decltype(full)::value) stage_math(std::integral_constant<int, S>{});
+        else                                 stage_math(std::integral_constant<int, 4>{});
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(lds_x + (L::X_STAGE - buf) + xdst[i]) = xr[i];
     };
+    // The loop holds full stages only; a last stage of 4 k-steps (S = 8) follows it.  One variant of
+    // the stage inside the loop: the two would meet at the loop's end with their values in
+    // different registers, and the moves that reconcile them were 5 % of the loop's instructions.
+    constexpr std::true_type full_stage{};
+    if constexpr (HALVES == 2) {
 #pragma nounroll
-    for (int st = 0; st < n_stages; st += HALVES) {
-        stage(std::integral_constant<int, 0>{}, st);
-        if constexpr (HALVES == 2) {
-            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1);
+        for (int st = 0; st < n_stages; st += 2) {
+            stage(std::integral_constant<int, 0>{}, st, full_stage);
+            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1, full_stage);
+        }
+    } else {
+        const int n_full = n_ksteps / S;
+#pragma nounroll
+        for (int st = 0; st < n_full; ++st) stage(std::integral_constant<int, 0>{}, st, full_stage);
+        if constexpr (S > 4) {
+            if (n_full < n_stages) stage(std::integral_constant<int, 0>{}, n_full, std::false_type{});
         }
     }
 }
@@ -1693,7 +1702,7 @@ __device__ __forceinline__ void stream_loop_a8(f32x4 (&acc)[MB][4], const u32x4 
     const int n_stages = (n_ksteps + S - 1) / S;
     const i32x4 magic = {0x4B400000, 0x4B400000, 0x4B400000, 0x4B400000};
 
-    auto stage = [&](auto half, int st) {
+    auto stage = [&](auto half, int st, auto full) {
         constexpr int H = decltype(half)::value;
         __syncthreads();
         const int buf = (st & 1) * L::X_STAGE;
@@ -1749,20 +1758,29 @@ __device__ __forceinline__ void stream_loop_a8(f32x4 (&acc)[MB][4], const u32x4 
                 }
             }
         };
-        if constexpr (S > 4) {
-            if (n_ksteps - st * S >= S) stage_math(std::integral_constant<int, S>{});
-            else                        stage_math(std::integral_constant<int, 4>{});
-        } else {
-            stage_math(std::integral_constant<int, S>{});
-        }
+        // (a unit is a whole number of 4-k-step super-steps: a stage of 8 k-steps is full, or the
+        // unit's last one with 4)
+        if constexpr (decltype(full)::value) stage_math(std::integral_constant<int, S>{});
+        else                                 stage_math(std::integral_constant<int, 4>{});
 #pragma unroll
         for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(lds_x + (L::X_STAGE - buf) + xdst[i]) = shuffled(xr[i]);
     };
+    // The loop holds full stages only; a last stage of 4 k-steps (S = 8) follows it.  One variant of
+    // the stage inside the loop: the two would meet at the loop's end with their values in
+    // different registers, and the moves that reconcile them were 5 % of the loop's instructions.
+    constexpr std::true_type full_stage{};
+    if constexpr (HALVES == 2) {
 #pragma nounroll
-    for (int st = 0; st < n_stages; st += HALVES) {
-        stage(std::integral_constant<int, 0>{}, st);
-        if constexpr (HALVES == 2) {
-            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1);
+        for (int st = 0; st < n_stages; st += 2) {
+            stage(std::integral_constant<int, 0>{}, st, full_stage);
+            if (st + 1 < n_stages) stage(std::integral_constant<int, 1>{}, st + 1, full_stage);
+        }
+    } else {
+        const int n_full = n_ksteps / S;
+#pragma nounroll
+        for (int st = 0; st < n_full; ++st) stage(std::integral_constant<int, 0>{}, st, full_stage);
+        if constexpr (S > 4) {
+            if (n_full < n_stages) stage(std::integral_constant<int, 0>{}, n_full, std::false_type{});
         }
     }
 }
