@@ -2022,7 +2022,9 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) {
                         if (!((r.sames[b] >> (16 * mb)) & 0xFFFFull)) continue;
-                        const bool mine = (r.sames[b] >> (16 * mb + l16)) & 1ull;
+                        // (a lane whose ranks lie past the adapter's takes zeros of t: its part of
+                        // B, a re-read of the first ranks, then needs no masking of its own)
+                        const bool mine = k_ok && ((r.sames[b] >> (16 * mb + l16)) & 1ull);
                         float tv[8];
                         // (16-byte aligned: rows of t are 528 bytes apart, a lane's run starts at a multiple of 32)
                         const f32x4_t *trow = reinterpret_cast<const f32x4_t *>(tl + (16 * mb + l16) * L::T_STRIDE + 32 * kk + 8 * lq);
@@ -2036,7 +2038,7 @@ __device__ __forceinline__ void wide_unit(const LayerArgs &a, const ProjArgs &P,
                         split_bf16(tv, thi, tlo);
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const uint4 b4 = k_ok ? __builtin_bit_cast(uint4, bf[b][j]) : make_uint4(0, 0, 0, 0);
+                            const uint4 b4 = __builtin_bit_cast(uint4, bf[b][j]);
                             acc[mb][j] = mfma16(thi, b4, acc[mb][j]);
                             acc[mb][j] = mfma16(tlo, b4, acc[mb][j]);
                         }
