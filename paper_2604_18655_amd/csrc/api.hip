@@ -71,11 +71,12 @@ int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 1
 // K chunks of the shrink step (at most MAX_KCHUNKS).  Decode shapes: 1024 inputs per chunk, split
 // over the four waves of a block (8 k-steps each, requested at once).  More than 16 rows: a wave
 // works through a chunk on its own for every row tile it is dealt; measured best with 512 inputs
-// per chunk up to 32 rows (the finishing blocks need t early there) and 1024 in the wide kernel
-// (fewer partial sums for every finishing block to gather).
-int kch_of(const mlora_w4_proj &p, int M)
+// per chunk for tile blocks of 17 to 32 rows (the finishing blocks need t early there) and 1024 in
+// the wide kernel at any row count (fewer shrink blocks and fewer partial sums for every unit to
+// gather: the 16-layer decode launch at 32 rows 198.0 -> 192.3 us; 2048: 196 us).
+int kch_of(const mlora_w4_proj &p, int M, bool wide)
 {
-    const int c = p.K / ((M > 16 && M <= 32) ? 512 : 1024);
+    const int c = p.K / ((M > 16 && M <= 32 && !wide) ? 512 : 1024);
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 
@@ -250,7 +251,7 @@ static mlora_status plan_launch(const mlora_w4_proj *projs, const void *const *x
             const size_t part_bytes = partial_bytes(p, M, wide, lb);
             // (two chunks of 16 rows have twice the rows of the shapes the per-row shrink blocks were
             // laid out for: at most 4 K chunks then, which also keeps the sum over them on its short path)
-            const int kch = chunk16 && kch_of(p, Mc) > 4 ? 4 : kch_of(p, Mc);
+            const int kch = chunk16 && kch_of(p, Mc, wide) > 4 ? 4 : kch_of(p, Mc, wide);
             const size_t t_bytes = lora ? round_up((size_t)kch * (size_t)M * (size_t)r16_of(p) * sizeof(float), 256) : 0;
             const int n_shrink = !lora ? 0
                 : (Mc <= 16 && !wide ? M : (M + SHRINK_CHUNK_ROWS - 1) / SHRINK_CHUNK_ROWS * shrink_tile_shares(M, p.n_adapters)) *
