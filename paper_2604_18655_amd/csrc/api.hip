@@ -73,10 +73,11 @@ int r16_of(const mlora_w4_proj &p) { return p.n_adapters > 0 ? (p.rank + 15) / 1
 // works through a chunk on its own for every row tile it is dealt; measured best with 512 inputs
 // per chunk for tile blocks of 17 to 32 rows (the finishing blocks need t early there) and 1024 in
 // the wide kernel at any row count (fewer shrink blocks and fewer partial sums for every unit to
-// gather: the 16-layer decode launch at 32 rows 198.0 -> 192.3 us; 2048: 196 us).
+// gather: the 16-layer decode launch at 32 rows 198.0 -> 192.3 us; 2048 everywhere: 196 us), and
+// 2048 where K is above 4096 (a projection of 14336 inputs at 64 rows: 14 -> 7 chunks, 64.1 -> 55.0 us).
 int kch_of(const mlora_w4_proj &p, int M, bool wide)
 {
-    const int c = p.K / ((M > 16 && M <= 32 && !wide) ? 512 : 1024);
+    const int c = p.K / ((M > 16 && M <= 32 && !wide) ? 512 : (wide && p.K > 4096) ? 2048 : 1024);
     return c < 1 ? 1 : (c > MAX_KCHUNKS ? MAX_KCHUNKS : c);
 }
 
