@@ -71,9 +71,10 @@ def test_workspace_bytes():
     p = proj(K=16384, rank=64)
     # (+ one counter line per (tile, row chunk) of a split-K projection: 1 tile x 1 chunk)
     # (33 rows and more, chunks of 64 rows: a launch this small is cut further, here into 32
-    # units of 4 x 128 inputs; the shrink step leaves 16 chunks of partial sums)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == need(lines(1, 1), 16 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
-    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == need(lines(1, 1), 16 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
+    # units of 4 x 128 inputs; the wide kernel's shrink step works on chunks of 2048 inputs where K
+    # is above 4096 and leaves 8 chunks of partial sums)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 64) == need(lines(1, 1), 8 * 64 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
+    assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 40) == need(lines(1, 1), 8 * 40 * 64 * 4 + 31 * 1 * 64 * 64 * 4)
     # (17 to 32 rows, a short launch: two chunks of 16 rows, 8 units of 2048 inputs, a shrink block
     # per row with at most 4 K chunks)
     assert cdll.mlora_w4_workspace_bytes(C.byref(p), 1, 24) == need(lines(1, 2), 4 * 24 * 64 * 4 + 7 * 1 * 32 * 64 * 4)
